@@ -1,0 +1,95 @@
+"""TEST INFRASTRUCTURE: the fp64 CPU checker for ``Y = A.X`` and ``A^l.X``.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this package.  It shares no code with the GPU library
+and imports nothing from it.
+
+* :func:`spmm`, :func:`spmm_iter` -- ctypes wrappers of ``spmm_oracle.c``
+  (plain CSR loops in fp64 over the original, undecomposed operand).
+* :mod:`oracle.arrow_checks` -- host-side checks of a decomposition
+  (bit-exact reassembly, arrow shape, injective permutations) and a slow
+  evaluation of ``sum_i P_i^T B_i P_i X`` used to validate exported levels.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is missing: build it with "
+                               "`python -m paper_2307_05740_amd._build oracle`")
+        lib = ctypes.CDLL(_LIB_PATH)
+        vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+        lib.oracle_spmm.restype = ctypes.c_int
+        lib.oracle_spmm.argtypes = [i64, vp, vp, vp, vp, i64, i32, i64, vp, vp, vp]
+        lib.oracle_spmm_iter.restype = ctypes.c_int
+        lib.oracle_spmm_iter.argtypes = [i64, vp, vp, vp, vp, i32, i32, vp, vp]
+        lib.oracle_num_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _csr(rowptr, colidx, vals):
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
+    colidx = np.ascontiguousarray(colidx, dtype=np.int32)
+    vals = np.ascontiguousarray(vals, dtype=np.float32)
+    assert rowptr.ndim == 1 and rowptr.shape[0] >= 1
+    assert colidx.shape[0] == vals.shape[0] == int(rowptr[-1])
+    return rowptr, colidx, vals
+
+
+def spmm(rowptr, colidx, vals, X, rows=None, c0: int = 0, kc: int | None = None):
+    """fp64 ``A.X`` and the bound ``|A|.|X|``.
+
+    ``rows``: optional int64 array selecting output rows (result row r is row
+    ``rows[r]`` of the product); ``c0, kc``: optional column slice of X.
+    Returns ``(Y, B)``, both float64 of shape (len(rows) or n, kc).
+    """
+    rowptr, colidx, vals = _csr(rowptr, colidx, vals)
+    n = rowptr.shape[0] - 1
+    assert X.dtype == np.float32 and X.ndim == 2 and X.flags.c_contiguous and X.shape[0] == n
+    k = X.shape[1]
+    kc = k - c0 if kc is None else kc
+    assert 0 <= c0 and kc >= 1 and c0 + kc <= k
+    if rows is None:
+        nrows, rows_ptr = n, None
+    else:
+        rows = np.ascontiguousarray(rows, dtype=np.int64)
+        nrows, rows_ptr = rows.shape[0], rows.ctypes.data
+    Y = np.empty((nrows, kc), dtype=np.float64)
+    B = np.empty((nrows, kc), dtype=np.float64)
+    rc = _load().oracle_spmm(n, rowptr.ctypes.data, colidx.ctypes.data, vals.ctypes.data,
+                             X.ctypes.data + 4 * c0, k, kc, nrows, rows_ptr,
+                             Y.ctypes.data, B.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"oracle_spmm failed ({rc})")
+    return Y, B
+
+
+def spmm_iter(rowptr, colidx, vals, X, l: int):
+    """fp64 ``A^l.X`` (never rounded to fp32 between products) and ``|A|^l.|X|``."""
+    rowptr, colidx, vals = _csr(rowptr, colidx, vals)
+    n = rowptr.shape[0] - 1
+    assert X.dtype == np.float32 and X.ndim == 2 and X.flags.c_contiguous and X.shape[0] == n
+    k = X.shape[1]
+    Xl = np.empty((n, k), dtype=np.float64)
+    El = np.empty((n, k), dtype=np.float64)
+    rc = _load().oracle_spmm_iter(n, rowptr.ctypes.data, colidx.ctypes.data, vals.ctypes.data,
+                                  X.ctypes.data, k, l, Xl.ctypes.data, El.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"oracle_spmm_iter failed ({rc})")
+    return Xl, El
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())

@@ -1,0 +1,205 @@
+"""Pins for the fp64 CPU checker (``oracle/``): it is compared with things other than itself.
+
+* exact rational brute force on tiny dense operands (non-symmetric, empty row, full row/column),
+* a hand-worked 3 x 3 product and the 3 x 3 grid fixture under ``tests/golden``,
+* operands whose product is known bit for bit (identity, permutation, diagonal, unit vectors),
+* closed forms (row-stochastic operand, grid operator row sums and sine eigenvectors, powers),
+* a library CSR product (scipy) in float64.
+
+A dropped term, a wrong sign, a transposed operand or an off-by-one in the row pointers fails
+at least one of these.
+"""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import scipy.sparse as sp
+
+import oracle
+from paper_2307_05740_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def random_csr(rng, n, density, full_row=None, full_col=None, empty_row=None):
+    M = (rng.random((n, n)) < density)
+    if full_row is not None:
+        M[full_row, :] = True
+    if full_col is not None:
+        M[:, full_col] = True
+    if empty_row is not None:
+        M[empty_row, :] = False
+    V = np.where(M, rng.uniform(-1, 1, (n, n)), 0.0).astype(np.float32)
+    rowptr = np.zeros(n + 1, np.int64)
+    cols, vals = [], []
+    for i in range(n):
+        for j in range(n):
+            if M[i, j]:
+                cols.append(j)
+                vals.append(V[i, j])
+        rowptr[i + 1] = len(cols)
+    return rowptr, np.array(cols, np.int32), np.array(vals, np.float32), V
+
+
+def exact_product(V, X):
+    """Y and |A||X| in exact rational arithmetic from the dense fp32 arrays."""
+    n, k = X.shape
+    Y = [[Fraction(0)] * k for _ in range(n)]
+    B = [[Fraction(0)] * k for _ in range(n)]
+    for i in range(n):
+        for j in range(n):
+            a = Fraction(float(V[i, j]))
+            if a == 0:
+                continue
+            for c in range(k):
+                x = Fraction(float(X[j, c]))
+                Y[i][c] += a * x
+                B[i][c] += abs(a) * abs(x)
+    return Y, B
+
+
+@pytest.mark.parametrize("n,k,density,seed", [(7, 3, 0.4, 1), (33, 5, 0.15, 2), (64, 4, 0.3, 3)])
+def test_brute_force_exact_rational(n, k, density, seed):
+    rng = np.random.default_rng(seed)
+    rowptr, colidx, vals, V = random_csr(rng, n, density, full_row=1, full_col=2, empty_row=n - 1)
+    X = rng.standard_normal((n, k)).astype(np.float32)
+    Y, B = oracle.spmm(rowptr, colidx, vals, X)
+    Ye, Be = exact_product(V, X)
+    u = 2.0 ** -53
+    for i in range(n):
+        for c in range(k):
+            # fp64 recursive summation of m exactly-representable products: error <= m*u*B
+            assert abs(Fraction(Y[i, c]) - Ye[i][c]) <= Fraction(n * u) * Be[i][c]
+            assert abs(Fraction(B[i, c]) - Be[i][c]) <= Fraction(n * u) * Be[i][c]
+    assert np.all(Y[n - 1] == 0) and np.all(B[n - 1] == 0)      # the empty row
+
+
+def test_transposed_operand_is_detected():
+    """The brute force distinguishes A from its transpose (operand is not symmetric)."""
+    rng = np.random.default_rng(11)
+    rowptr, colidx, vals, V = random_csr(rng, 16, 0.3)
+    X = rng.standard_normal((16, 2)).astype(np.float32)
+    Y, _ = oracle.spmm(rowptr, colidx, vals, X)
+    assert np.allclose(Y, V.astype(np.float64) @ X.astype(np.float64), rtol=0, atol=1e-12)
+    assert not np.allclose(Y, V.T.astype(np.float64) @ X.astype(np.float64), atol=1e-3)
+
+
+def test_golden_hand_3x3():
+    rec = {}
+    for line in open(os.path.join(GOLDEN, "hand_3x3_product.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, *nums = line.split()
+        rec[name] = np.array([float(t) for t in nums])
+    X = rec["X"].reshape(3, 2).astype(np.float32)
+    Y, B = oracle.spmm(rec["A_rowptr"].astype(np.int64), rec["A_colidx"].astype(np.int32),
+                       rec["A_vals"].astype(np.float32), X)
+    assert np.array_equal(Y, rec["Y"].reshape(3, 2))
+    assert np.array_equal(B, rec["B"].reshape(3, 2))
+
+
+def test_golden_grid3_times_ones():
+    want = np.loadtxt(os.path.join(GOLDEN, "grid3_times_ones.txt")).reshape(9, 1)
+    rp, ci = synth.grid5_pattern(3)
+    Y, B = oracle.spmm(rp, ci, synth.fill_grid5(rp, ci), np.ones((9, 1), np.float32))
+    assert np.array_equal(Y, want)
+    assert np.array_equal(B, 8.0 - want)          # |A| row sums: 4 + number of neighbours
+
+
+def test_identity_permutation_diagonal_bitwise():
+    rng = np.random.default_rng(5)
+    n, k = 50, 6
+    X = rng.standard_normal((n, k)).astype(np.float32)
+    rp = np.arange(n + 1, dtype=np.int64)
+    ones = np.ones(n, np.float32)
+    Y, B = oracle.spmm(rp, np.arange(n, dtype=np.int32), ones, X)
+    assert np.array_equal(Y, X.astype(np.float64)) and np.array_equal(B, np.abs(X, dtype=np.float64))
+    perm = rng.permutation(n).astype(np.int32)
+    Y, _ = oracle.spmm(rp, perm, ones, X)               # row i holds a 1 in column perm[i]
+    assert np.array_equal(Y, X[perm].astype(np.float64))
+    d = rng.uniform(-2, 2, n).astype(np.float32)
+    Y, _ = oracle.spmm(rp, np.arange(n, dtype=np.int32), d, X)
+    assert np.array_equal(Y, d.astype(np.float64)[:, None] * X.astype(np.float64))  # exact in fp64
+
+
+def test_unit_vector_columns_give_columns_of_A():
+    rng = np.random.default_rng(6)
+    n = 24
+    rowptr, colidx, vals, V = random_csr(rng, n, 0.25)
+    Y, _ = oracle.spmm(rowptr, colidx, vals, np.eye(n, dtype=np.float32))
+    assert np.array_equal(Y, V.astype(np.float64))
+
+
+def test_row_stochastic_times_ones():
+    rp, ci = synth.rmat_pattern(10, 8 << 10, seed=3)
+    vals = synth.fill_row_normalized(rp)
+    n = rp.shape[0] - 1
+    nonempty = np.diff(rp) > 0
+    Y, B = oracle.spmm(rp, ci, vals, np.ones((n, 2), np.float32))
+    assert np.allclose(Y[nonempty], 1.0, rtol=0, atol=2e-7) and np.all(Y[~nonempty] == 0)
+    assert np.array_equal(Y, B)                      # all terms are non-negative
+    Xl, El = oracle.spmm_iter(rp, ci, vals, np.ones((n, 2), np.float32), 4)
+    reach = Xl[:, 0] != 0                            # rows whose walks never hit an empty row
+    assert np.allclose(Xl[reach & nonempty], 1.0, rtol=0, atol=1e-6)
+
+
+@pytest.mark.parametrize("N,p,q", [(8, 1, 1), (12, 2, 5), (17, 17, 3)])
+def test_grid_operator_sine_eigenvectors_and_powers(N, p, q):
+    rp, ci = synth.grid5_pattern(N)
+    vals = synth.fill_grid5(rp, ci)
+    xs = np.arange(1, N + 1)
+    v = np.outer(np.sin(np.pi * q * xs / (N + 1)), np.sin(np.pi * p * xs / (N + 1))).reshape(-1, 1)
+    lam = 4 - 2 * np.cos(np.pi * p / (N + 1)) - 2 * np.cos(np.pi * q / (N + 1))
+    v32 = v.astype(np.float32)
+    Y, B = oracle.spmm(rp, ci, vals, v32)
+    # v32 differs from the eigenvector by fp32 rounding only: residual <= |A| * 2^-24 per term
+    assert np.all(np.abs(Y - lam * v32.astype(np.float64)) <= 2.0 ** -23 * (B + 1e-30) + 1e-12)
+    for l in (0, 1, 2, 5):
+        Xl, El = oracle.spmm_iter(rp, ci, vals, v32, l)
+        assert np.all(np.abs(Xl - lam ** l * v32.astype(np.float64)) <= 2.0 ** -22 * El + 1e-12), l
+        assert np.all(El >= np.abs(Xl) - 1e-12)
+
+
+def test_library_csr_product_and_iterates():
+    w = synth.make_config(0)                          # R-MAT scale 12, uniform values
+    X = w.make_x()
+    A = sp.csr_matrix((w.vals.astype(np.float64), w.colidx, w.rowptr), shape=(w.n, w.n))
+    Y, B = oracle.spmm(w.rowptr, w.colidx, w.vals, X)
+    Ylib = A @ X.astype(np.float64)
+    Blib = abs(A) @ np.abs(X.astype(np.float64))
+    assert np.all(np.abs(Y - Ylib) <= 1e-13 * Blib)
+    assert np.all(np.abs(B - Blib) <= 1e-13 * Blib)
+    Xl, El = oracle.spmm_iter(w.rowptr, w.colidx, w.vals, X, 3)
+    assert np.all(np.abs(Xl - A @ (A @ Ylib)) <= 1e-12 * (abs(A) @ (abs(A) @ Blib)))
+    assert np.all(np.abs(El - abs(A) @ (abs(A) @ Blib)) <= 1e-12 * El)
+
+
+def test_row_selection_and_column_slice_agree_with_full():
+    w = synth.make_config(0)
+    X = w.make_x()
+    Y, B = oracle.spmm(w.rowptr, w.colidx, w.vals, X)
+    rows = np.array([0, 5, 4095, 17, 17], np.int64)
+    Ys, Bs = oracle.spmm(w.rowptr, w.colidx, w.vals, X, rows=rows, c0=3, kc=7)
+    assert np.array_equal(Ys, Y[rows, 3:10]) and np.array_equal(Bs, B[rows, 3:10])
+    X0, E0 = oracle.spmm_iter(w.rowptr, w.colidx, w.vals, X, 0)
+    assert np.array_equal(X0, X.astype(np.float64)) and np.array_equal(E0, np.abs(X0))
+    X1, E1 = oracle.spmm_iter(w.rowptr, w.colidx, w.vals, X, 1)
+    assert np.array_equal(X1, Y) and np.array_equal(E1, B)
+
+
+def test_linearity_and_symmetry_identities():
+    w = synth.make_config(0, shrink=2)
+    X = w.make_x()
+    A = (w.rowptr, w.colidx, w.vals)
+    Y, B = oracle.spmm(*A, X)
+    X2 = synth.normal_matrix(w.n, w.k, seed=99)
+    Y2, B2 = oracle.spmm(*A, X2)
+    # the pattern is symmetric but the values are not: use A + A^T through both products
+    M = sp.csr_matrix((w.vals.astype(np.float64), w.colidx, w.rowptr), shape=(w.n, w.n))
+    lhs = np.sum(X2.astype(np.float64) * Y)                 # <X2, A X>
+    rhs = np.sum((M.T @ X2.astype(np.float64)) * X)         # <A^T X2, X>
+    assert abs(lhs - rhs) <= 1e-10 * np.sum(B * np.abs(X2))
+    Xs = (2.0 * X + X2).astype(np.float32)                  # exact? no: rounded, so use the bound
+    Ys, Bs = oracle.spmm(*A, Xs)
+    assert np.all(np.abs(Ys - (2 * Y + Y2)) <= 2.0 ** -22 * (2 * B + B2) + 1e-30)
