@@ -1,0 +1,204 @@
+/*
+ * arrow.h -- C boundary of the arrow-matrix-decomposition SpMM library for one
+ * MI355X (gfx950).
+ *
+ * The operation.  For a square sparse A (n x n, CSR, fp32) and a tall-skinny
+ * dense X (n x k, fp32, row-major) the library computes Y = A.X, the order-2,
+ * single-term member of the kernel class of the paper's section "SpTTN
+ * Kernels" (one sparse operand contracted with dense operands into a dense
+ * output); CSR is the order-2 case of the storage of section "Tensor Sparsity
+ * and Sparse Storage".  One product is counted as 2.nnz.k operations (section
+ * "Pairwise Contraction").  The product is not evaluated on A directly but as
+ *
+ *        Y = sum_{i < L}  P_i^T . B_i . (P_i . X)
+ *
+ * where (P_i X)[p,:] = X[perm_i[p],:] selects and reorders n_i <= n rows, and
+ * every B_i is an ARROW MATRIX of width b: a stored entry (p,q) of B_i has
+ * p/b == q/b (diagonal block), or p < b (first block row, the "head" rows), or
+ * q < b (first block column).  The paper itself does not define this
+ * decomposition; the definition used here is: the head of a level holds the
+ * highest-degree vertices of what is still unassigned (plus block separators
+ * when they make the level complete), the rest are laid out by a linear
+ * arrangement and cut into blocks of b; entries that fit the arrow shape
+ * belong to the level, all others go on to the next level.  Each nonzero of A
+ * lands in exactly one level, unchanged.
+ *
+ * Conventions.
+ *  - "host" pointers are ordinary CPU memory, "device" pointers are HIP device
+ *    memory of the current device.  The library allocates no device memory:
+ *    the caller provides the image buffer and the workspace and keeps them
+ *    alive until arrow_destroy().
+ *  - X and Y are contiguous row-major with leading dimension k and must be
+ *    16-byte aligned.  Y is overwritten (never accumulated into).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Compute calls only enqueue work on it and return without synchronising.
+ *    A handle may be used from one stream at a time.
+ *  - Every call returns ARROW_OK (0) or a negative arrow_status; nothing
+ *    throws or aborts.  arrow_last_error() gives a thread-local description
+ *    of the last failure.
+ */
+#ifndef ARROW_H
+#define ARROW_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum arrow_status {
+  ARROW_OK = 0,
+  ARROW_EINVAL = -1,    /* bad argument: n<=0, b<=0, k<=0, l<0, NULL, malformed CSR */
+  ARROW_ENOMEM = -2,    /* host allocation failed                                   */
+  ARROW_ENOTREADY = -3, /* compute call before arrow_upload / arrow_set_workspace   */
+  ARROW_ETOOSMALL = -4, /* a caller-provided buffer is smaller than required        */
+  ARROW_EHIP = -5,      /* a HIP runtime call failed (text in arrow_last_error)     */
+  ARROW_EINTERNAL = -6  /* a self-check of the decomposition failed                 */
+} arrow_status;
+
+typedef struct arrow_handle arrow_handle; /* opaque, host memory, owned by the library */
+
+/* Whole-decomposition figures. */
+typedef struct arrow_info_t {
+  int64_t n;          /* rows = columns of A                         */
+  int64_t nnz;        /* stored entries of A                         */
+  int32_t b;          /* arrow width                                 */
+  int32_t levels;     /* L, number of arrow matrices                 */
+  int64_t max_chunks; /* largest number of head partials of a level  */
+  double decompose_seconds;
+} arrow_info_t;
+
+/* Figures of one level i. Regions partition the stored entries of B_i. */
+typedef struct arrow_level_info_t {
+  int64_t n_i;          /* active vertices = length of perm_i                    */
+  int64_t nnz;          /* stored entries of B_i                                 */
+  int64_t nnz_head_head;/* p < b and q < b                                       */
+  int64_t nnz_head_row; /* p < b and q >= b  (first block row, off the corner)   */
+  int64_t nnz_head_col; /* p >= b and q < b  (first block column)                */
+  int64_t nnz_diag;     /* p >= b and q >= b (then p/b == q/b)                   */
+  int64_t short_rows;   /* rows handled one per lane group                       */
+  int64_t chunks;       /* nonzero chunks handled one per wavefront              */
+  int64_t split_rows;   /* rows whose chunks are combined by the reduction pass  */
+  int64_t partials;     /* partial vectors those rows produce (one per chunk)    */
+  int64_t nnz_rows;     /* entries held by the lane-group row list               */
+  int64_t nnz_chunks;   /* entries held by the chunk list                        */
+  int64_t x_rows_rows;  /* distinct rows of X the row list reads                 */
+  int64_t x_rows_chunks;/* distinct rows of X the chunk list reads               */
+  int32_t blocks;       /* ceil(n_i / b)                                         */
+  int32_t separator_rule; /* 1 if block separators were promoted into the head   */
+} arrow_level_info_t;
+
+/* Per-kernel-class time of the last profiled product, milliseconds. */
+typedef struct arrow_profile_t {
+  float rows_ms;    /* lane-group-per-row kernel (first block column + diagonal blocks, short head rows) */
+  float chunks_ms;  /* wavefront-per-chunk kernel (head rows and other long rows)                         */
+  float reduce_ms;  /* cross-chunk reduction + scatter                                                    */
+  float window_ms;  /* diagonal blocks with the X window staged in LDS                                    */
+  float total_ms;   /* first launch to last launch of the product                                         */
+  int32_t rows_launches, chunks_launches, reduce_launches, window_launches; /* launches per class (one per level that has such work) */
+} arrow_profile_t;
+
+/*
+ * Decompose A into arrow matrices of width b (host only, no GPU needed).
+ *   n        rows = columns, 1 <= n <= 2^31 - 2
+ *   rowptr   host, n+1 entries, rowptr[0] == 0, non-decreasing, rowptr[n] = nnz < 2^32 - 1
+ *   colidx   host, nnz entries in [0,n), strictly increasing inside every row
+ *   vals     host, nnz fp32 values (explicit zeros are kept as entries)
+ *   b        arrow width >= 1 (b >= n gives one level with B_0 = A reordered)
+ *   out      receives the handle; the CSR arrays are not referenced after return
+ * Errors: ARROW_EINVAL (any violated condition above), ARROW_ENOMEM.
+ */
+int arrow_decompose(int64_t n, const int64_t *rowptr, const int32_t *colidx,
+                    const float *vals, int32_t b, arrow_handle **out);
+
+/* Bytes of device memory the packed image (tiles, work lists, permutations) needs. 0 if h is NULL. */
+size_t arrow_device_bytes(const arrow_handle *h);
+
+/*
+ * Copy the packed image into caller-owned device memory (256-byte aligned,
+ * at least arrow_device_bytes(h)) with an asynchronous copy on `stream`, and
+ * bind the handle to it.  The source is the handle's pageable host copy, so the
+ * call may block until the copy has been staged.  Errors: EINVAL, ETOOSMALL, EHIP.
+ */
+int arrow_upload(arrow_handle *h, void *dev_buf, size_t bytes, void *stream);
+
+/*
+ * Device workspace a product with k columns needs: head partials of the
+ * largest level plus one n x k buffer for the chained products of
+ * arrow_spmm_iter.  arrow_set_workspace binds caller-owned device memory
+ * (256-byte aligned); it may be rebound at any time the stream is idle.
+ */
+size_t arrow_workspace_bytes(const arrow_handle *h, int32_t k);
+int arrow_set_workspace(arrow_handle *h, void *dev_ws, size_t bytes);
+
+/*
+ * Y = A.X = sum_i P_i^T B_i (P_i X).   X, Y: device, n x k fp32, must not overlap.
+ * Level 0 stores every row of Y (perm_0 is a full permutation); later levels
+ * add into the rows they touch, in stream order, so the result does not
+ * depend on scheduling (no floating-point atomics are used).
+ * Errors: EINVAL (NULL, k < 1, X == Y), ENOTREADY, ETOOSMALL (workspace bound
+ * for a smaller k), EHIP.
+ */
+int arrow_spmm(arrow_handle *h, const float *X, float *Y, int32_t k, void *stream);
+
+/*
+ * X <- A^l . X, l chained products rounded to fp32 after each one, result left
+ * in X (l = 0 leaves X untouched).  Uses the n x k part of the workspace.
+ * Errors as arrow_spmm, plus EINVAL for l < 0.
+ */
+int arrow_spmm_iter(arrow_handle *h, float *X, int32_t k, int32_t l, void *stream);
+
+/*
+ * The permutation gather of one level on its own: Xp[p,:] = X[perm_i[p],:]
+ * for p < n_i.  X: device n x k; Xp: device n_i x k.  The products above fuse
+ * this step into their loads; it is exported for layouts that want P_i X
+ * materialised and for testing.  Errors: EINVAL, ENOTREADY, EHIP.
+ */
+int arrow_gather(arrow_handle *h, int32_t level, const float *X, float *Xp,
+                 int32_t k, void *stream);
+
+/* Introspection (host only). */
+int arrow_info(const arrow_handle *h, arrow_info_t *out);
+int arrow_level_info(const arrow_handle *h, int32_t level, arrow_level_info_t *out);
+
+/*
+ * Host copies of one level for checking: perm (n_i entries, position ->
+ * original vertex) and the stored entries of B_i as coordinate triples in
+ * position space (rows/cols/vals, nnz_i entries each).  Any output pointer may
+ * be NULL to skip it.  Errors: EINVAL.
+ */
+int arrow_export_level(const arrow_handle *h, int32_t level, int32_t *perm,
+                       int32_t *rows, int32_t *cols, float *vals);
+
+/*
+ * Launch-time tunables, by name:
+ *   "kc"        columns per pass (0 = automatic: min(k, 64 lanes x 4 columns)); a smaller slice
+ *               shrinks the working set of X rows per pass and re-reads the entries k/kc times
+ *   "xcd_remap" 1 (default): consecutive work items run on the same accelerator die
+ * Pack-time choices are read from the environment by arrow_decompose: ARROW_SHORT_MAX (rows
+ * with at most this many entries are handled one per lane group, default 16), ARROW_CHUNK_NNZ
+ * (entries per wavefront chunk, default 512), ARROW_SEPARATORS and ARROW_BFS_TAIL (0 disables
+ * the separator rule / the breadth-first arrangement of later levels).
+ * Errors: EINVAL (unknown name, value out of range).
+ */
+int arrow_set_option(arrow_handle *h, const char *name, int64_t value);
+
+/*
+ * Profiling: when enabled, every product brackets its launches with HIP
+ * events on the caller's stream; arrow_get_profile waits for them and
+ * reports per-kernel-class times of the most recent product.
+ */
+int arrow_set_profiling(arrow_handle *h, int32_t enabled);
+int arrow_get_profile(arrow_handle *h, arrow_profile_t *out);
+
+/* Thread-local text of the last error ("" if none). Never NULL. */
+const char *arrow_last_error(void);
+
+/* Release the handle and its host memory (not the caller's device buffers). NULL is ignored. */
+void arrow_destroy(arrow_handle *h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ARROW_H */

@@ -1,0 +1,267 @@
+"""ctypes binding of ``libarrow.so`` (declared in ``include/arrow.h``).
+
+Argument marshalling only: every step of a product runs in the library's HIP
+kernels.  The functions carry the C names; :class:`ArrowSpMM` is a small
+convenience that owns the torch tensors used as device memory (image and
+workspace) for one handle.  There is no CPU fallback: if the shared library is
+missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libarrow.so")
+_lib = None
+
+ARROW_OK, ARROW_EINVAL, ARROW_ENOMEM, ARROW_ENOTREADY, ARROW_ETOOSMALL, ARROW_EHIP, ARROW_EINTERNAL = \
+    0, -1, -2, -3, -4, -5, -6
+
+EXPORTED = [
+    "arrow_decompose", "arrow_device_bytes", "arrow_upload", "arrow_workspace_bytes",
+    "arrow_set_workspace", "arrow_spmm", "arrow_spmm_iter", "arrow_gather", "arrow_info",
+    "arrow_level_info", "arrow_export_level", "arrow_set_option", "arrow_set_profiling",
+    "arrow_get_profile", "arrow_last_error", "arrow_destroy",
+]
+
+
+class ArrowError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"arrow error {code}: {text}")
+        self.code = code
+
+
+class arrow_info_t(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int64), ("nnz", ctypes.c_int64), ("b", ctypes.c_int32),
+                ("levels", ctypes.c_int32), ("max_chunks", ctypes.c_int64),
+                ("decompose_seconds", ctypes.c_double)]
+
+
+class arrow_level_info_t(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_int64) for name in
+                ("n_i", "nnz", "nnz_head_head", "nnz_head_row", "nnz_head_col", "nnz_diag",
+                 "short_rows", "chunks", "split_rows", "partials", "nnz_rows", "nnz_chunks",
+                 "x_rows_rows", "x_rows_chunks")] + \
+               [("blocks", ctypes.c_int32), ("separator_rule", ctypes.c_int32)]
+
+
+class arrow_profile_t(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_float) for name in
+                ("rows_ms", "chunks_ms", "reduce_ms", "window_ms", "total_ms")] + \
+               [(name, ctypes.c_int32) for name in
+                ("rows_launches", "chunks_launches", "reduce_launches", "window_launches")]
+
+
+def lib():
+    """Load ``libarrow.so``; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                           "`python -m paper_2307_05740_amd._build arrow` (no CPU fallback exists)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+    L.arrow_decompose.restype = ctypes.c_int
+    L.arrow_decompose.argtypes = [i64, vp, vp, vp, i32, ctypes.POINTER(vp)]
+    L.arrow_device_bytes.restype = sz
+    L.arrow_device_bytes.argtypes = [vp]
+    L.arrow_upload.restype = ctypes.c_int
+    L.arrow_upload.argtypes = [vp, vp, sz, vp]
+    L.arrow_workspace_bytes.restype = sz
+    L.arrow_workspace_bytes.argtypes = [vp, i32]
+    L.arrow_set_workspace.restype = ctypes.c_int
+    L.arrow_set_workspace.argtypes = [vp, vp, sz]
+    L.arrow_spmm.restype = ctypes.c_int
+    L.arrow_spmm.argtypes = [vp, vp, vp, i32, vp]
+    L.arrow_spmm_iter.restype = ctypes.c_int
+    L.arrow_spmm_iter.argtypes = [vp, vp, i32, i32, vp]
+    L.arrow_gather.restype = ctypes.c_int
+    L.arrow_gather.argtypes = [vp, i32, vp, vp, i32, vp]
+    L.arrow_info.restype = ctypes.c_int
+    L.arrow_info.argtypes = [vp, ctypes.POINTER(arrow_info_t)]
+    L.arrow_level_info.restype = ctypes.c_int
+    L.arrow_level_info.argtypes = [vp, i32, ctypes.POINTER(arrow_level_info_t)]
+    L.arrow_export_level.restype = ctypes.c_int
+    L.arrow_export_level.argtypes = [vp, i32, vp, vp, vp, vp]
+    L.arrow_set_option.restype = ctypes.c_int
+    L.arrow_set_option.argtypes = [vp, ctypes.c_char_p, i64]
+    L.arrow_set_profiling.restype = ctypes.c_int
+    L.arrow_set_profiling.argtypes = [vp, i32]
+    L.arrow_get_profile.restype = ctypes.c_int
+    L.arrow_get_profile.argtypes = [vp, ctypes.POINTER(arrow_profile_t)]
+    L.arrow_last_error.restype = ctypes.c_char_p
+    L.arrow_last_error.argtypes = []
+    L.arrow_destroy.restype = None
+    L.arrow_destroy.argtypes = [vp]
+    _lib = L
+    return L
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise ArrowError(rc, lib().arrow_last_error().decode())
+
+
+def arrow_last_error() -> str:
+    return lib().arrow_last_error().decode()
+
+
+def arrow_decompose(rowptr: np.ndarray, colidx: np.ndarray, vals: np.ndarray, b: int,
+                    n: int | None = None) -> int:
+    """Host CSR (int64 rowptr, int32 colidx, float32 vals) -> opaque handle (an integer address)."""
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
+    colidx = np.ascontiguousarray(colidx, dtype=np.int32)
+    vals = np.ascontiguousarray(vals, dtype=np.float32)
+    n = rowptr.shape[0] - 1 if n is None else n
+    out = ctypes.c_void_p()
+    _check(lib().arrow_decompose(n, rowptr.ctypes.data, colidx.ctypes.data, vals.ctypes.data, b,
+                                 ctypes.byref(out)))
+    return out.value
+
+
+def arrow_device_bytes(h: int) -> int:
+    return int(lib().arrow_device_bytes(h))
+
+
+def arrow_upload(h: int, dev_ptr: int, nbytes: int, stream: int = 0) -> None:
+    _check(lib().arrow_upload(h, dev_ptr, nbytes, stream))
+
+
+def arrow_workspace_bytes(h: int, k: int) -> int:
+    return int(lib().arrow_workspace_bytes(h, k))
+
+
+def arrow_set_workspace(h: int, dev_ptr: int, nbytes: int) -> None:
+    _check(lib().arrow_set_workspace(h, dev_ptr, nbytes))
+
+
+def arrow_spmm(h: int, x_ptr: int, y_ptr: int, k: int, stream: int = 0) -> None:
+    _check(lib().arrow_spmm(h, x_ptr, y_ptr, k, stream))
+
+
+def arrow_spmm_iter(h: int, x_ptr: int, k: int, l: int, stream: int = 0) -> None:
+    _check(lib().arrow_spmm_iter(h, x_ptr, k, l, stream))
+
+
+def arrow_gather(h: int, level: int, x_ptr: int, xp_ptr: int, k: int, stream: int = 0) -> None:
+    _check(lib().arrow_gather(h, level, x_ptr, xp_ptr, k, stream))
+
+
+def arrow_info(h: int) -> dict:
+    out = arrow_info_t()
+    _check(lib().arrow_info(h, ctypes.byref(out)))
+    return {f: getattr(out, f) for f, _ in out._fields_}
+
+
+def arrow_level_info(h: int, level: int) -> dict:
+    out = arrow_level_info_t()
+    _check(lib().arrow_level_info(h, level, ctypes.byref(out)))
+    return {f: getattr(out, f) for f, _ in out._fields_}
+
+
+def arrow_export_level(h: int, level: int):
+    """Host copies ``(perm, rows, cols, vals)`` of level ``level`` in position coordinates."""
+    info = arrow_level_info(h, level)
+    perm = np.empty(info["n_i"], dtype=np.int32)
+    rows = np.empty(info["nnz"], dtype=np.int32)
+    cols = np.empty(info["nnz"], dtype=np.int32)
+    vals = np.empty(info["nnz"], dtype=np.float32)
+    _check(lib().arrow_export_level(h, level, perm.ctypes.data, rows.ctypes.data, cols.ctypes.data,
+                                    vals.ctypes.data))
+    return perm, rows, cols, vals
+
+
+def arrow_set_option(h: int, name: str, value: int) -> None:
+    _check(lib().arrow_set_option(h, name.encode(), value))
+
+
+def arrow_set_profiling(h: int, enabled: bool) -> None:
+    _check(lib().arrow_set_profiling(h, 1 if enabled else 0))
+
+
+def arrow_get_profile(h: int) -> dict:
+    out = arrow_profile_t()
+    _check(lib().arrow_get_profile(h, ctypes.byref(out)))
+    return {f: getattr(out, f) for f, _ in out._fields_}
+
+
+def arrow_destroy(h: int) -> None:
+    lib().arrow_destroy(h)
+
+
+class ArrowSpMM:
+    """One decomposed operand bound to torch-owned device memory (plumbing only)."""
+
+    def __init__(self, rowptr, colidx, vals, b: int, device="cuda:0"):
+        import torch
+        self._torch = torch
+        self.device = torch.device(device)
+        self.h = arrow_decompose(rowptr, colidx, vals, b)
+        self.info = arrow_info(self.h)
+        self.n = self.info["n"]
+        nbytes = arrow_device_bytes(self.h)
+        with torch.cuda.device(self.device):
+            self._image = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
+            arrow_upload(self.h, self._image.data_ptr(), self._image.numel(), self._stream())
+            torch.cuda.current_stream().synchronize()
+        self._ws = None
+        self._ws_k = 0
+
+    def _stream(self) -> int:
+        return self._torch.cuda.current_stream(self.device).cuda_stream
+
+    def _ensure_workspace(self, k: int) -> None:
+        if self._ws is not None and self._ws_k >= k:
+            return
+        torch = self._torch
+        torch.cuda.current_stream(self.device).synchronize()
+        nbytes = arrow_workspace_bytes(self.h, k)
+        self._ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
+        self._ws_k = k
+        arrow_set_workspace(self.h, self._ws.data_ptr(), self._ws.numel())
+
+    def levels(self):
+        return [arrow_level_info(self.h, i) for i in range(self.info["levels"])]
+
+    def spmm(self, X, Y=None):
+        torch = self._torch
+        assert X.is_cuda and X.dtype == torch.float32 and X.dim() == 2 and X.is_contiguous()
+        assert X.shape[0] == self.n
+        k = X.shape[1]
+        if Y is None:
+            Y = torch.empty_like(X)
+        assert Y.shape == X.shape and Y.dtype == torch.float32 and Y.is_contiguous()
+        self._ensure_workspace(k)
+        arrow_spmm(self.h, X.data_ptr(), Y.data_ptr(), k, self._stream())
+        return Y
+
+    def spmm_iter(self, X, l: int):
+        torch = self._torch
+        assert X.is_cuda and X.dtype == torch.float32 and X.dim() == 2 and X.is_contiguous()
+        assert X.shape[0] == self.n
+        self._ensure_workspace(X.shape[1])
+        arrow_spmm_iter(self.h, X.data_ptr(), X.shape[1], l, self._stream())
+        return X
+
+    def gather(self, level: int, X):
+        torch = self._torch
+        n_i = arrow_level_info(self.h, level)["n_i"]
+        Xp = torch.empty((n_i, X.shape[1]), dtype=torch.float32, device=self.device)
+        arrow_gather(self.h, level, X.data_ptr(), Xp.data_ptr(), X.shape[1], self._stream())
+        return Xp
+
+    def close(self) -> None:
+        if self.h:
+            self._torch.cuda.synchronize(self.device)
+            arrow_destroy(self.h)
+            self.h = 0
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

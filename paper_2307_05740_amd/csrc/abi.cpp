@@ -1,0 +1,383 @@
+// C boundary: handle lifetime, validation, upload, the level loop of
+//   Y = sum_i P_i^T B_i (P_i X)
+// and the chained products.  All arithmetic of a product happens in the HIP
+// kernels this file launches; nothing here falls back to the CPU.
+#include <hip/hip_runtime.h>
+#include <omp.h>
+
+#include <chrono>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "arrow.h"
+#include "arrow_internal.h"
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+int64_t env_int(const char* name, int64_t dflt) {
+  const char* s = std::getenv(name);
+  if (!s || !*s) return dflt;
+  char* end = nullptr;
+  long long v = std::strtoll(s, &end, 10);
+  return (end && *end == 0) ? (int64_t)v : dflt;
+}
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+enum KernelClass { kRows = 0, kChunks = 1, kReduce = 2, kWindow = 3, kClasses = 4 };
+
+struct Span {
+  int cls;
+  hipEvent_t a, b;
+};
+
+}  // namespace
+
+struct arrow_handle {
+  int64_t n = 0, nnz = 0;
+  int32_t b = 0;
+  std::vector<arrow::HostLevel> levels;
+  arrow::Image img;
+  arrow::PackOptions pack;
+  arrow::LaunchTuning tuning;
+  double decompose_seconds = 0.0;
+  // device bindings (caller-owned memory)
+  unsigned char* dev = nullptr;
+  unsigned char* ws = nullptr;
+  size_t ws_bytes = 0;
+  // profiling
+  bool profiling = false;
+  std::vector<Span> spans;   // event pool, reused between products
+  size_t spans_used = 0;
+};
+
+namespace {
+
+size_t partial_bytes(const arrow_handle* h, int32_t k) {
+  return align_up((size_t)h->img.max_partials * (size_t)k * sizeof(float));
+}
+
+template <typename T>
+const T* at(const arrow_handle* h, size_t off) {
+  return reinterpret_cast<const T*>(h->dev + off);
+}
+
+// start/stop one profiled launch
+struct Scoped {
+  arrow_handle* h;
+  hipStream_t s;
+  Span* sp = nullptr;
+  Scoped(arrow_handle* h_, int cls, hipStream_t s_) : h(h_), s(s_) {
+    if (!h->profiling) return;
+    if (h->spans_used == h->spans.size()) {
+      Span n{cls, nullptr, nullptr};
+      if (hipEventCreate(&n.a) != hipSuccess || hipEventCreate(&n.b) != hipSuccess) return;
+      h->spans.push_back(n);
+    }
+    sp = &h->spans[h->spans_used++];
+    sp->cls = cls;
+    (void)hipEventRecord(sp->a, s);
+  }
+  ~Scoped() {
+    if (sp) (void)hipEventRecord(sp->b, s);
+  }
+};
+
+int check_hip(int rc, const char* what) {
+  if (rc == 0) return ARROW_OK;
+  return fail(ARROW_EHIP, "%s: %s", what, hipGetErrorString((hipError_t)rc));
+}
+
+// one product, src -> dst (device, n x k), all levels in stream order
+int product(arrow_handle* h, const float* X, float* Y, int32_t k, hipStream_t stream) {
+  float* partials = reinterpret_cast<float*>(h->ws);
+  for (size_t li = 0; li < h->img.levels.size(); ++li) {
+    const arrow::LevelImage& im = h->img.levels[li];
+    const bool acc = li > 0;
+    const arrow::Entry* ent = at<arrow::Entry>(h, im.off_entries);
+    if (im.n_chunks > 0) {
+      Scoped sc(h, kChunks, stream);
+      int rc = arrow::launch_chunks(at<uint32_t>(h, im.off_chunk_ptr), at<int32_t>(h, im.off_chunk_dst),
+                                    ent, im.n_chunks, X, Y, partials, k, acc, h->tuning, stream);
+      if (rc) return check_hip(rc, "chunks kernel launch");
+    }
+    if (im.n_rows > 0) {
+      Scoped sc(h, kRows, stream);
+      int rc = arrow::launch_rows(at<uint32_t>(h, im.off_rows_ptr), at<int32_t>(h, im.off_rows_y), ent,
+                                  im.n_rows, X, Y, k, acc, h->tuning, stream);
+      if (rc) return check_hip(rc, "rows kernel launch");
+    }
+    if (im.n_split > 0) {
+      Scoped sc(h, kReduce, stream);
+      int rc = arrow::launch_reduce(at<uint32_t>(h, im.off_split_ptr), at<int32_t>(h, im.off_split_y),
+                                    im.n_split, partials, Y, k, acc, stream);
+      if (rc) return check_hip(rc, "reduce kernel launch");
+    }
+  }
+  return ARROW_OK;
+}
+
+int ready(const arrow_handle* h, int32_t k, bool need_iter_buffer) {
+  if (!h) return fail(ARROW_EINVAL, "handle is NULL");
+  if (k < 1) return fail(ARROW_EINVAL, "k must be >= 1 (got %d)", k);
+  if (!h->dev) return fail(ARROW_ENOTREADY, "arrow_upload has not been called");
+  if (!h->ws) return fail(ARROW_ENOTREADY, "arrow_set_workspace has not been called");
+  size_t need = partial_bytes(h, k);
+  if (need_iter_buffer) need += (size_t)h->n * (size_t)k * sizeof(float);
+  if (h->ws_bytes < need)
+    return fail(ARROW_ETOOSMALL, "workspace holds %zu bytes, k = %d needs %zu", h->ws_bytes, k, need);
+  return ARROW_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* arrow_last_error(void) { return g_err.c_str(); }
+
+int arrow_decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const float* vals,
+                    int32_t b, arrow_handle** out) {
+  if (!out) return fail(ARROW_EINVAL, "out is NULL");
+  *out = nullptr;
+  if (n < 1 || n > 2147483646LL) return fail(ARROW_EINVAL, "n must be in [1, 2^31 - 2] (got %lld)", (long long)n);
+  if (b < 1) return fail(ARROW_EINVAL, "b must be >= 1 (got %d)", b);
+  if (!rowptr) return fail(ARROW_EINVAL, "rowptr is NULL");
+  if (rowptr[0] != 0) return fail(ARROW_EINVAL, "rowptr[0] must be 0");
+  const int64_t nnz = rowptr[n];
+  if (nnz < 0 || nnz >= 0xffffffffLL) return fail(ARROW_EINVAL, "nnz must be in [0, 2^32 - 2]");
+  if (nnz > 0 && (!colidx || !vals)) return fail(ARROW_EINVAL, "colidx / vals is NULL");
+  int64_t bad_row = -1;
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < n; ++i) {
+    bool ok = rowptr[i] <= rowptr[i + 1] && rowptr[i] >= 0 && rowptr[i + 1] <= nnz;
+    if (ok)
+      for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) {
+        int32_t c = colidx[p];
+        if (c < 0 || c >= n || (p > rowptr[i] && colidx[p - 1] >= c)) { ok = false; break; }
+      }
+    if (!ok) {
+#pragma omp critical
+      if (bad_row < 0 || i < bad_row) bad_row = i;
+    }
+  }
+  if (bad_row >= 0)
+    return fail(ARROW_EINVAL, "malformed CSR at row %lld (row pointers must not decrease; column ids "
+                "must be in range and strictly increasing inside a row)", (long long)bad_row);
+
+  arrow_handle* h = new (std::nothrow) arrow_handle;
+  if (!h) return fail(ARROW_ENOMEM, "out of host memory");
+  h->n = n; h->nnz = nnz; h->b = b;
+  arrow::DecomposeOptions dopt;
+  dopt.separators = env_int("ARROW_SEPARATORS", 1) != 0;
+  dopt.bfs_tail = env_int("ARROW_BFS_TAIL", 1) != 0;
+  h->pack.short_max = (int32_t)env_int("ARROW_SHORT_MAX", h->pack.short_max);
+  h->pack.chunk_nnz = (int32_t)env_int("ARROW_CHUNK_NNZ", h->pack.chunk_nnz);
+  h->tuning.kc = (int32_t)env_int("ARROW_KC", 0);
+  h->tuning.xcd_remap = (int32_t)env_int("ARROW_XCD_REMAP", 1);
+  std::string err;
+  int rc;
+  try {
+    auto t0 = std::chrono::steady_clock::now();
+    rc = arrow::decompose(n, rowptr, colidx, vals, b, dopt, h->levels, err);
+    if (rc == ARROW_OK) rc = arrow::pack_image(n, b, h->levels, h->pack, h->img, err);
+    h->decompose_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+  } catch (const std::bad_alloc&) {
+    rc = ARROW_ENOMEM;
+    err = "out of host memory during decomposition";
+  }
+  if (rc != ARROW_OK) {
+    delete h;
+    return fail(rc, "%s", err.c_str());
+  }
+  *out = h;
+  return ARROW_OK;
+}
+
+size_t arrow_device_bytes(const arrow_handle* h) { return h ? h->img.bytes.size() : 0; }
+
+int arrow_upload(arrow_handle* h, void* dev_buf, size_t bytes, void* stream) {
+  if (!h) return fail(ARROW_EINVAL, "handle is NULL");
+  if (!dev_buf) return fail(ARROW_EINVAL, "dev_buf is NULL");
+  if ((uintptr_t)dev_buf % kAlign) return fail(ARROW_EINVAL, "dev_buf must be 256-byte aligned");
+  if (bytes < h->img.bytes.size())
+    return fail(ARROW_ETOOSMALL, "image needs %zu bytes, buffer has %zu", h->img.bytes.size(), bytes);
+  if (!h->img.bytes.empty()) {
+    hipError_t e = hipMemcpyAsync(dev_buf, h->img.bytes.data(), h->img.bytes.size(),
+                                  hipMemcpyHostToDevice, (hipStream_t)stream);
+    if (e != hipSuccess) return check_hip((int)e, "image upload");
+  }
+  h->dev = static_cast<unsigned char*>(dev_buf);
+  return ARROW_OK;
+}
+
+size_t arrow_workspace_bytes(const arrow_handle* h, int32_t k) {
+  if (!h || k < 1) return 0;
+  return partial_bytes(h, k) + align_up((size_t)h->n * (size_t)k * sizeof(float));
+}
+
+int arrow_set_workspace(arrow_handle* h, void* dev_ws, size_t bytes) {
+  if (!h) return fail(ARROW_EINVAL, "handle is NULL");
+  if (!dev_ws) return fail(ARROW_EINVAL, "dev_ws is NULL");
+  if ((uintptr_t)dev_ws % kAlign) return fail(ARROW_EINVAL, "dev_ws must be 256-byte aligned");
+  h->ws = static_cast<unsigned char*>(dev_ws);
+  h->ws_bytes = bytes;
+  return ARROW_OK;
+}
+
+int arrow_spmm(arrow_handle* h, const float* X, float* Y, int32_t k, void* stream) {
+  int rc = ready(h, k, false);
+  if (rc) return rc;
+  if (!X || !Y) return fail(ARROW_EINVAL, "X or Y is NULL");
+  if (X == Y) return fail(ARROW_EINVAL, "X and Y must not overlap");
+  if (((uintptr_t)X | (uintptr_t)Y) % 16) return fail(ARROW_EINVAL, "X and Y must be 16-byte aligned");
+  h->spans_used = 0;
+  return product(h, X, Y, k, (hipStream_t)stream);
+}
+
+int arrow_spmm_iter(arrow_handle* h, float* X, int32_t k, int32_t l, void* stream) {
+  if (l < 0) return fail(ARROW_EINVAL, "l must be >= 0 (got %d)", l);
+  int rc = ready(h, k, l > 0);
+  if (rc) return rc;
+  if (!X) return fail(ARROW_EINVAL, "X is NULL");
+  if ((uintptr_t)X % 16) return fail(ARROW_EINVAL, "X must be 16-byte aligned");
+  if (l == 0) return ARROW_OK;
+  h->spans_used = 0;
+  float* tmp = reinterpret_cast<float*>(h->ws + partial_bytes(h, k));
+  float* src = X;
+  float* dst = tmp;
+  for (int32_t t = 0; t < l; ++t) {
+    rc = product(h, src, dst, k, (hipStream_t)stream);
+    if (rc) return rc;
+    float* s = src; src = dst; dst = s;
+  }
+  if (src != X) {   // odd l: the last product landed in the workspace
+    hipError_t e = hipMemcpyAsync(X, src, (size_t)h->n * (size_t)k * sizeof(float),
+                                  hipMemcpyDeviceToDevice, (hipStream_t)stream);
+    if (e != hipSuccess) return check_hip((int)e, "copy of the last iterate");
+  }
+  return ARROW_OK;
+}
+
+int arrow_gather(arrow_handle* h, int32_t level, const float* X, float* Xp, int32_t k, void* stream) {
+  if (!h) return fail(ARROW_EINVAL, "handle is NULL");
+  if (level < 0 || (size_t)level >= h->img.levels.size()) return fail(ARROW_EINVAL, "no level %d", level);
+  if (k < 1 || !X || !Xp) return fail(ARROW_EINVAL, "bad X / Xp / k");
+  if (((uintptr_t)X | (uintptr_t)Xp) % 16) return fail(ARROW_EINVAL, "X and Xp must be 16-byte aligned");
+  if (!h->dev) return fail(ARROW_ENOTREADY, "arrow_upload has not been called");
+  const arrow::LevelImage& im = h->img.levels[level];
+  int rc = arrow::launch_gather(at<int32_t>(h, im.off_perm), im.n_i, X, Xp, k, stream);
+  return check_hip(rc, "gather kernel launch");
+}
+
+int arrow_info(const arrow_handle* h, arrow_info_t* out) {
+  if (!h || !out) return fail(ARROW_EINVAL, "NULL argument");
+  out->n = h->n; out->nnz = h->nnz; out->b = h->b;
+  out->levels = (int32_t)h->levels.size();
+  out->max_chunks = h->img.max_partials;
+  out->decompose_seconds = h->decompose_seconds;
+  return ARROW_OK;
+}
+
+int arrow_level_info(const arrow_handle* h, int32_t level, arrow_level_info_t* out) {
+  if (!h || !out) return fail(ARROW_EINVAL, "NULL argument");
+  if (level < 0 || (size_t)level >= h->levels.size()) return fail(ARROW_EINVAL, "no level %d", level);
+  const arrow::HostLevel& L = h->levels[level];
+  const arrow::LevelImage& im = h->img.levels[level];
+  out->n_i = L.n_i;
+  out->nnz = L.rowptr[L.n_i];
+  out->nnz_head_head = L.nnz_head_head; out->nnz_head_row = L.nnz_head_row;
+  out->nnz_head_col = L.nnz_head_col; out->nnz_diag = L.nnz_diag;
+  out->short_rows = im.n_rows; out->chunks = im.n_chunks; out->split_rows = im.n_split;
+  out->partials = im.n_partials; out->nnz_rows = im.nnz_rows; out->nnz_chunks = im.nnz_chunks;
+  out->x_rows_rows = im.x_rows_rows; out->x_rows_chunks = im.x_rows_chunks;
+  out->blocks = (int32_t)((L.n_i + h->b - 1) / h->b);
+  out->separator_rule = L.separator_rule ? 1 : 0;
+  return ARROW_OK;
+}
+
+int arrow_export_level(const arrow_handle* h, int32_t level, int32_t* perm, int32_t* rows,
+                       int32_t* cols, float* vals) {
+  if (!h) return fail(ARROW_EINVAL, "handle is NULL");
+  if (level < 0 || (size_t)level >= h->levels.size()) return fail(ARROW_EINVAL, "no level %d", level);
+  const arrow::HostLevel& L = h->levels[level];
+  const int64_t nnz = L.rowptr[L.n_i];
+  if (perm) std::memcpy(perm, L.perm.data(), sizeof(int32_t) * (size_t)L.n_i);
+  if (cols && nnz) std::memcpy(cols, L.colpos.data(), sizeof(int32_t) * (size_t)nnz);
+  if (vals && nnz) std::memcpy(vals, L.vals.data(), sizeof(float) * (size_t)nnz);
+  if (rows) {
+#pragma omp parallel for schedule(static)
+    for (int64_t p = 0; p < L.n_i; ++p)
+      for (int64_t e = L.rowptr[p]; e < L.rowptr[p + 1]; ++e) rows[e] = (int32_t)p;
+  }
+  return ARROW_OK;
+}
+
+int arrow_set_option(arrow_handle* h, const char* name, int64_t value) {
+  if (!h || !name) return fail(ARROW_EINVAL, "NULL argument");
+  if (!std::strcmp(name, "kc")) {
+    if (value < 0 || value > 256) return fail(ARROW_EINVAL, "kc must be in [0, 256]");
+    h->tuning.kc = (int32_t)value;
+  } else if (!std::strcmp(name, "xcd_remap")) {
+    h->tuning.xcd_remap = value ? 1 : 0;
+  } else {
+    return fail(ARROW_EINVAL, "unknown option '%s'", name);
+  }
+  return ARROW_OK;
+}
+
+int arrow_set_profiling(arrow_handle* h, int32_t enabled) {
+  if (!h) return fail(ARROW_EINVAL, "handle is NULL");
+  h->profiling = enabled != 0;
+  h->spans_used = 0;
+  return ARROW_OK;
+}
+
+int arrow_get_profile(arrow_handle* h, arrow_profile_t* out) {
+  if (!h || !out) return fail(ARROW_EINVAL, "NULL argument");
+  std::memset(out, 0, sizeof *out);
+  if (h->spans_used == 0) return fail(ARROW_ENOTREADY, "no profiled product has run");
+  hipError_t e = hipEventSynchronize(h->spans[h->spans_used - 1].b);
+  if (e != hipSuccess) return check_hip((int)e, "event synchronize");
+  float* slot[kClasses] = {&out->rows_ms, &out->chunks_ms, &out->reduce_ms, &out->window_ms};
+  int32_t* count[kClasses] = {&out->rows_launches, &out->chunks_launches, &out->reduce_launches,
+                              &out->window_launches};
+  for (size_t i = 0; i < h->spans_used; ++i) {
+    float ms = 0.f;
+    e = hipEventElapsedTime(&ms, h->spans[i].a, h->spans[i].b);
+    if (e != hipSuccess) return check_hip((int)e, "event elapsed time");
+    *slot[h->spans[i].cls] += ms;
+    *count[h->spans[i].cls] += 1;
+  }
+  e = hipEventElapsedTime(&out->total_ms, h->spans[0].a, h->spans[h->spans_used - 1].b);
+  if (e != hipSuccess) return check_hip((int)e, "event elapsed time");
+  return ARROW_OK;
+}
+
+void arrow_destroy(arrow_handle* h) {
+  if (!h) return;
+  for (Span& s : h->spans) {
+    if (s.a) (void)hipEventDestroy(s.a);
+    if (s.b) (void)hipEventDestroy(s.b);
+  }
+  delete h;
+}
+
+}  // extern "C"

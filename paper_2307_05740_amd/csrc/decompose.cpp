@@ -1,0 +1,268 @@
+// Host-side arrow decomposition: A = sum_i P_i^T B_i P_i with every B_i an
+// arrow matrix of width b (diagonal blocks of b positions, plus the first
+// block row and the first block column).
+//
+// The paper does not define this decomposition; what is implemented is the
+// following peeling, repeated on the entries no earlier level has taken:
+//   1. degree of a vertex = its remaining off-diagonal entries, row plus column;
+//      the active vertices are those with any remaining entry (level 0: all).
+//   2. the remaining vertices are put in a linear arrangement: ascending id at
+//      level 0, breadth-first order over the remainder at later levels.
+//   3. head (positions 0..b-1), one of two rules:
+//        separator rule - hubs (degree > hub_factor * mean) first, then walk
+//          the arrangement filling blocks of b; a vertex with an entry into an
+//          already closed block is moved to the head.  If the head does not
+//          overflow, the level captures every remaining entry; spare head
+//          positions are filled from the end of the arrangement, which moves
+//          no block boundary.
+//        plain rule - the b vertices of highest degree (ties: lower id first);
+//          everything else keeps its arrangement order and is cut into blocks.
+//   4. an entry (u,v) belongs to the level iff pos(u) < b or pos(v) < b or
+//      pos(u)/b == pos(v)/b; the others form the next remainder.
+// The plain rule always captures every entry of the maximum-degree vertex, so
+// each level removes at least one entry and the loop ends.  Values are moved,
+// never combined: every stored entry of A appears in exactly one level.
+#include "arrow_internal.h"
+
+#include <omp.h>
+
+#include <algorithm>
+#include <cstring>
+#include <numeric>
+
+#include "arrow.h"
+
+namespace arrow {
+namespace {
+
+struct Remainder {
+  // CSR over original vertex ids of the entries still unassigned
+  const int64_t* ptr = nullptr;
+  const int32_t* col = nullptr;
+  const float* val = nullptr;
+  std::vector<int64_t> own_ptr;
+  std::vector<int32_t> own_col;
+  std::vector<float> own_val;
+  int64_t nnz(int64_t n) const { return ptr[n]; }
+};
+
+// breadth-first arrangement of the active vertices over the remainder's rows
+void bfs_order(int64_t n, const Remainder& R, const std::vector<uint8_t>& active,
+               std::vector<int32_t>& order) {
+  std::vector<uint8_t> seen(n, 0);
+  order.clear();
+  for (int64_t s = 0; s < n; ++s) {
+    if (!active[s] || seen[s]) continue;
+    size_t head = order.size();
+    order.push_back((int32_t)s);
+    seen[s] = 1;
+    while (head < order.size()) {
+      int32_t u = order[head++];
+      for (int64_t p = R.ptr[u]; p < R.ptr[u + 1]; ++p) {
+        int32_t w = R.col[p];
+        if (!seen[w] && active[w]) { seen[w] = 1; order.push_back(w); }
+      }
+    }
+  }
+}
+
+}  // namespace
+
+int decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const float* vals,
+              int32_t b, const DecomposeOptions& opt, std::vector<HostLevel>& levels,
+              std::string& err) {
+  levels.clear();
+  Remainder R;
+  R.ptr = rowptr; R.col = colidx; R.val = vals;
+
+  std::vector<int32_t> pos(n);
+  std::vector<int64_t> deg(n);
+  std::vector<int32_t> colcnt(n);
+  std::vector<uint8_t> active(n);
+  std::vector<int32_t> order;
+  const int64_t level_cap = 4 * ((n + b - 1) / b) + 64;
+
+  for (int64_t lev = 0;; ++lev) {
+    const int64_t rem_nnz = R.nnz(n);
+    if (lev > 0 && rem_nnz == 0) break;
+    if (lev > level_cap) { err = "decomposition did not terminate"; return ARROW_EINTERNAL; }
+
+    // ---- 1. degrees and active set ---------------------------------------
+    std::fill(colcnt.begin(), colcnt.end(), 0);
+#pragma omp parallel for schedule(dynamic, 4096)
+    for (int64_t u = 0; u < n; ++u)
+      for (int64_t p = R.ptr[u]; p < R.ptr[u + 1]; ++p)
+        __atomic_fetch_add(&colcnt[R.col[p]], 1, __ATOMIC_RELAXED);
+    int64_t n_i = 0;
+    double deg_sum = 0.0;
+#pragma omp parallel for schedule(dynamic, 4096) reduction(+ : n_i, deg_sum)
+    for (int64_t u = 0; u < n; ++u) {
+      int64_t rc = R.ptr[u + 1] - R.ptr[u];
+      bool diag = std::binary_search(R.col + R.ptr[u], R.col + R.ptr[u + 1], (int32_t)u);
+      deg[u] = rc + colcnt[u] - (diag ? 2 : 0);
+      bool a = (lev == 0) || rc > 0 || colcnt[u] > 0;
+      active[u] = a;
+      if (a) { ++n_i; deg_sum += (double)deg[u]; }
+    }
+
+    HostLevel L;
+    L.n_i = n_i;
+    L.perm.resize(n_i);
+    std::fill(pos.begin(), pos.end(), -1);
+    auto by_degree = [&](int32_t x, int32_t y) {
+      return deg[x] != deg[y] ? deg[x] > deg[y] : x < y;
+    };
+
+    // ---- 2. arrangement ---------------------------------------------------
+    if (lev == 0 || !opt.bfs_tail) {
+      order.resize(0);
+      order.reserve(n_i);
+      for (int64_t u = 0; u < n; ++u) if (active[u]) order.push_back((int32_t)u);
+    } else {
+      bfs_order(n, R, active, order);
+    }
+
+    // ---- 3. head and block positions ------------------------------------
+    if (n_i <= b) {
+      std::sort(order.begin(), order.end(), by_degree);
+      for (int64_t p = 0; p < n_i; ++p) L.perm[p] = order[p];
+    } else {
+      bool done = false;
+      if (opt.separators) {
+        const double thresh = opt.hub_factor * (deg_sum / (double)n_i);
+        std::vector<int32_t> hubs;
+        for (int32_t v : order) if ((double)deg[v] > thresh) hubs.push_back(v);
+        if ((int64_t)hubs.size() < b) {
+          std::sort(hubs.begin(), hubs.end(), by_degree);
+          // block id per vertex: -1 unplaced, 0 head, r >= 1 body block r
+          std::vector<int32_t> blk(n, -1);
+          for (int32_t v : hubs) blk[v] = 0;
+          const int64_t cap = b - (int64_t)hubs.size();
+          std::vector<int32_t> seps, body;
+          body.reserve(n_i);
+          int32_t cur = 1;
+          int64_t fill = 0;
+          bool ok = true;
+          for (int32_t v : order) {
+            if (blk[v] == 0) continue;
+            bool promote = false;
+            for (int64_t p = R.ptr[v]; p < R.ptr[v + 1]; ++p) {
+              int32_t bw = blk[R.col[p]];
+              if (bw >= 1 && bw < cur) { promote = true; break; }
+            }
+            if (promote) {
+              if ((int64_t)seps.size() == cap) { ok = false; break; }
+              seps.push_back(v);
+              blk[v] = 0;
+            } else {
+              body.push_back(v);
+              blk[v] = cur;
+              if (++fill == b) { ++cur; fill = 0; }
+            }
+          }
+          if (ok) {
+            int64_t need = b - (int64_t)hubs.size() - (int64_t)seps.size();
+            int64_t h = 0;
+            for (int32_t v : hubs) L.perm[h++] = v;
+            for (int32_t v : seps) L.perm[h++] = v;
+            for (int64_t t = 0; t < need; ++t) { L.perm[h++] = body.back(); body.pop_back(); }
+            for (int32_t v : body) L.perm[h++] = v;
+            L.separator_rule = true;
+            done = true;
+          }
+        }
+      }
+      if (!done) {
+        std::vector<int32_t> cand(order);
+        std::nth_element(cand.begin(), cand.begin() + b, cand.end(), by_degree);
+        std::sort(cand.begin(), cand.begin() + b, by_degree);
+        std::vector<uint8_t> in_head(n, 0);
+        for (int64_t p = 0; p < b; ++p) { L.perm[p] = cand[p]; in_head[cand[p]] = 1; }
+        int64_t h = b;
+        for (int32_t v : order) if (!in_head[v]) L.perm[h++] = v;
+      }
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t p = 0; p < n_i; ++p) pos[L.perm[p]] = (int32_t)p;
+
+    // ---- 4. split the remainder into this level's arrow and the next remainder
+    auto in_arrow = [&](int64_t pu, int64_t pv) {
+      return pu < b || pv < b || pu / b == pv / b;
+    };
+    L.rowptr.assign(n_i + 1, 0);
+    std::vector<int64_t> next_ptr(n + 1, 0);
+#pragma omp parallel for schedule(dynamic, 4096)
+    for (int64_t u = 0; u < n; ++u) {
+      int64_t pu = pos[u];
+      if (pu < 0) continue;
+      int64_t keep = 0, drop = 0;
+      for (int64_t p = R.ptr[u]; p < R.ptr[u + 1]; ++p) {
+        if (in_arrow(pu, pos[R.col[p]])) ++keep; else ++drop;
+      }
+      L.rowptr[pu + 1] = keep;
+      next_ptr[u + 1] = drop;
+    }
+    for (int64_t p = 0; p < n_i; ++p) L.rowptr[p + 1] += L.rowptr[p];
+    for (int64_t u = 0; u < n; ++u) next_ptr[u + 1] += next_ptr[u];
+    const int64_t lev_nnz = L.rowptr[n_i];
+    const int64_t next_nnz = next_ptr[n];
+    if (lev_nnz + next_nnz != rem_nnz) { err = "entry count mismatch while peeling"; return ARROW_EINTERNAL; }
+    if (lev_nnz == 0 && rem_nnz > 0) { err = "a level captured no entry"; return ARROW_EINTERNAL; }
+    L.colpos.resize(lev_nnz);
+    L.vals.resize(lev_nnz);
+    std::vector<int32_t> next_col(next_nnz);
+    std::vector<float> next_val(next_nnz);
+    int64_t hh = 0, hr = 0, hc = 0, dg = 0;
+#pragma omp parallel for schedule(dynamic, 1024) reduction(+ : hh, hr, hc, dg)
+    for (int64_t u = 0; u < n; ++u) {
+      int64_t pu = pos[u];
+      if (pu < 0) continue;
+      int64_t w = L.rowptr[pu], x = next_ptr[u];
+      const int64_t w0 = w;
+      for (int64_t p = R.ptr[u]; p < R.ptr[u + 1]; ++p) {
+        int64_t pv = pos[R.col[p]];
+        if (in_arrow(pu, pv)) {
+          L.colpos[w] = (int32_t)pv;
+          L.vals[w] = R.val[p];
+          ++w;
+          if (pu < b) { if (pv < b) ++hh; else ++hr; } else { if (pv < b) ++hc; else ++dg; }
+        } else {
+          next_col[x] = R.col[p];
+          next_val[x] = R.val[p];
+          ++x;
+        }
+      }
+      // order the row by column position (keys are distinct inside a row)
+      const int64_t len = w - w0;
+      if (len > 1) {
+        bool sorted = true;
+        for (int64_t q = w0 + 1; q < w; ++q) if (L.colpos[q - 1] > L.colpos[q]) { sorted = false; break; }
+        if (!sorted) {
+          std::vector<uint64_t> key(len);
+          for (int64_t q = 0; q < len; ++q) {
+            uint32_t bits;
+            std::memcpy(&bits, &L.vals[w0 + q], 4);
+            key[q] = ((uint64_t)(uint32_t)L.colpos[w0 + q] << 32) | bits;
+          }
+          std::sort(key.begin(), key.end());
+          for (int64_t q = 0; q < len; ++q) {
+            L.colpos[w0 + q] = (int32_t)(key[q] >> 32);
+            uint32_t bits = (uint32_t)key[q];
+            std::memcpy(&L.vals[w0 + q], &bits, 4);
+          }
+        }
+      }
+    }
+    L.nnz_head_head = hh; L.nnz_head_row = hr; L.nnz_head_col = hc; L.nnz_diag = dg;
+    levels.push_back(std::move(L));
+
+    R.own_ptr.swap(next_ptr);
+    R.own_col.swap(next_col);
+    R.own_val.swap(next_val);
+    R.ptr = R.own_ptr.data(); R.col = R.own_col.data(); R.val = R.own_val.data();
+    if (next_nnz == 0) break;
+  }
+  return ARROW_OK;
+}
+
+}  // namespace arrow

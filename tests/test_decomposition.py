@@ -1,0 +1,211 @@
+"""Host-side checks of ``arrow_decompose`` (no GPU): the exported levels must reassemble A bit
+for bit, every level must have arrow shape of width b, and the slow fp64 evaluation of
+``sum_i P_i^T B_i P_i X`` over the exported levels must equal the CSR product of A."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import arrow_checks
+from paper_2307_05740_amd import _build, binding, synth
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib_built():
+    if not os.path.exists(_build.ARROW_LIB):
+        _build.build_arrow()
+
+
+def decompose_and_export(rowptr, colidx, vals, b):
+    h = binding.arrow_decompose(rowptr, colidx, vals, b)
+    try:
+        info = binding.arrow_info(h)
+        levels = [binding.arrow_export_level(h, i) for i in range(info["levels"])]
+        linfo = [binding.arrow_level_info(h, i) for i in range(info["levels"])]
+    finally:
+        binding.arrow_destroy(h)
+    return info, linfo, levels
+
+
+def full_check(rowptr, colidx, vals, b, X=None):
+    n = rowptr.shape[0] - 1
+    info, linfo, levels = decompose_and_export(rowptr, colidx, vals, b)
+    assert info["n"] == n and info["nnz"] == rowptr[-1] and info["b"] == b
+    arrow_checks.check_decomposition(n, rowptr, colidx, vals, b, levels)
+    assert len(levels[0][0]) == n                       # perm_0 is a full permutation
+    for (perm, r, c, v), li in zip(levels, linfo):
+        assert li["n_i"] == len(perm) and li["nnz"] == len(v)
+        assert li["nnz_head_head"] + li["nnz_head_row"] + li["nnz_head_col"] + li["nnz_diag"] == li["nnz"]
+        assert li["nnz_head_head"] == np.count_nonzero((r < b) & (c < b))
+        assert li["nnz_diag"] == np.count_nonzero((r >= b) & (c >= b))
+        key = r.astype(np.int64) * max(len(perm), 1) + c
+        assert np.all(np.diff(key) > 0)                 # rows ascending, columns ascending in a row
+    assert sum(li["nnz"] for li in linfo) == rowptr[-1]
+    if X is not None:
+        Y, B = oracle.spmm(rowptr, colidx, vals, X)
+        Ya = arrow_checks.arrow_product(n, levels, X)
+        assert np.all(np.abs(Ya - Y) <= 1e-12 * B + 1e-300)
+    return info, linfo, levels
+
+
+def csr_from_coo(n, rows, cols, vals):
+    order = np.lexsort((cols, rows))
+    rows, cols, vals = rows[order], cols[order], vals[order]
+    rowptr = np.zeros(n + 1, np.int64)
+    np.add.at(rowptr, rows + 1, 1)
+    return np.cumsum(rowptr), cols.astype(np.int32), vals.astype(np.float32)
+
+
+def test_config0_rmat():
+    w = synth.make_config(0)
+    info, linfo, _ = full_check(w.rowptr, w.colidx, w.vals, w.b, w.make_x())
+    assert 1 <= info["levels"] <= 8                      # never more than ceil(n / b) levels
+    assert linfo[0]["nnz"] > 0.8 * w.nnz                 # hubs in the head capture most entries
+    assert linfo[0]["blocks"] == 8
+
+
+@pytest.mark.parametrize("b", [1, 3, 64, 100, 4096, 10000])
+def test_block_widths_including_degenerate(b):
+    w = synth.make_config(0, shrink=2)                   # n = 1024
+    info, linfo, levels = full_check(w.rowptr, w.colidx, w.vals, b, w.make_x())
+    if b >= w.n:
+        assert info["levels"] == 1 and linfo[0]["nnz"] == w.nnz
+
+
+def test_grid_gives_one_arrow_matrix_with_separators():
+    w = synth.make_config(1, shrink=8)                   # 64 x 64 grid; b = 1024 = 16 grid rows,
+    info, linfo, _ = full_check(w.rowptr, w.colidx, w.vals, 1024, w.make_x())   # 3 separators fit
+    assert info["levels"] == 1 and linfo[0]["separator_rule"] == 1
+    assert linfo[0]["nnz_diag"] > 0.5 * w.nnz            # the stencil lives in the diagonal blocks
+
+
+def test_grid_plain_rule_needs_second_level(monkeypatch):
+    monkeypatch.setenv("ARROW_SEPARATORS", "0")
+    w = synth.make_config(1, shrink=8)
+    info, linfo, _ = full_check(w.rowptr, w.colidx, w.vals, 1024, w.make_x())
+    assert info["levels"] >= 2 and linfo[0]["separator_rule"] == 0
+
+
+def test_row_normalized_rmat_and_chung_lu_small():
+    for idx, shrink in ((2, 8), (4, 10)):
+        w = synth.make_config(idx, shrink=shrink)
+        info, linfo, _ = full_check(w.rowptr, w.colidx, w.vals, w.b, w.make_x()[:, :4].copy())
+        assert info["levels"] <= (w.n + w.b - 1) // w.b + 1
+
+
+def test_star_plus_short_paths_is_one_level():
+    # one hub joined to everything, plus disjoint paths shorter than b
+    n, b = 257, 16
+    rows, cols = [], []
+    for v in range(1, n):
+        rows += [0, v]; cols += [v, 0]
+    for start in range(1, n - 8, 8):
+        for v in range(start, start + 7):
+            rows += [v, v + 1]; cols += [v + 1, v]
+    rng = np.random.default_rng(0)
+    rp, ci, va = csr_from_coo(n, np.array(rows), np.array(cols), rng.uniform(-1, 1, len(rows)))
+    info, _, _ = full_check(rp, ci, va, b, rng.standard_normal((n, 3)).astype(np.float32))
+    assert info["levels"] == 1
+
+
+def test_block_diagonal_is_one_level_without_arrow_strips():
+    n, b = 96, 8
+    rng = np.random.default_rng(1)
+    rows, cols = [], []
+    for blk in range(n // b):
+        for i in range(b):
+            for j in range(b):
+                if rng.random() < 0.5 or i == j:
+                    rows.append(blk * b + i); cols.append(blk * b + j)
+    rp, ci, va = csr_from_coo(n, np.array(rows), np.array(cols), rng.uniform(-1, 1, len(rows)))
+    info, linfo, _ = full_check(rp, ci, va, b, rng.standard_normal((n, 2)).astype(np.float32))
+    assert info["levels"] == 1
+
+
+def test_single_crossing_entry_needs_two_levels_with_plain_rule(monkeypatch):
+    monkeypatch.setenv("ARROW_SEPARATORS", "0")
+    # a cycle-free chain of equal-degree vertices in two far-apart blocks plus one crossing pair
+    n, b = 64, 8
+    rows = list(range(n)); cols = list(range(n))          # diagonal only: all degrees 0
+    rows += [20, 50]; cols += [50, 20]                    # crossing entries between blocks 2 and 6
+    rows += [3, 4]; cols += [4, 3]                        # a pair with the same degree but lower ids
+    rp, ci, va = csr_from_coo(n, np.array(rows), np.array(cols), np.arange(1, len(rows) + 1, dtype=np.float64))
+    info, linfo, levels = full_check(rp, ci, va, b, np.eye(n, dtype=np.float32)[:, :5].copy())
+    assert info["levels"] == 1    # degree-1 vertices sort ahead of degree-0 ones, so they are in the head
+    # now make the head too small to take them all: b = 2 and three disjoint far pairs
+    rows = list(range(n)); cols = list(range(n))
+    for u, v in ((10, 40), (20, 50), (30, 60)):
+        rows += [u, v]; cols += [v, u]
+    rp, ci, va = csr_from_coo(n, np.array(rows), np.array(cols), np.arange(1, len(rows) + 1, dtype=np.float64))
+    info, _, _ = full_check(rp, ci, va, 2, np.eye(n, dtype=np.float32)[:, :5].copy())
+    assert info["levels"] == 2
+
+
+def test_nonsymmetric_operand():
+    rng = np.random.default_rng(4)
+    n = 200
+    M = rng.random((n, n)) < 0.03
+    r, c = np.nonzero(M)
+    rp, ci, va = csr_from_coo(n, r, c, rng.uniform(-1, 1, len(r)))
+    full_check(rp, ci, va, 16, rng.standard_normal((n, 3)).astype(np.float32))
+    full_check(rp, ci, va, 7, rng.standard_normal((n, 3)).astype(np.float32))
+
+
+def test_empty_matrix_and_explicit_zeros():
+    n = 10
+    rp = np.zeros(n + 1, np.int64)
+    info, linfo, levels = full_check(rp, np.zeros(0, np.int32), np.zeros(0, np.float32), 4,
+                                     np.ones((n, 2), np.float32))
+    assert info["levels"] == 1 and linfo[0]["nnz"] == 0
+    rp, ci, va = csr_from_coo(3, np.array([0, 1, 2]), np.array([2, 1, 0]), np.array([0.0, -0.0, 1.0]))
+    full_check(rp, ci, va, 1, np.ones((3, 1), np.float32))       # signed zeros survive bit-exactly
+
+
+def test_error_paths():
+    w = synth.make_config(0, shrink=4)
+    bad = [
+        dict(b=0), dict(n=0), dict(rowptr=w.rowptr[::-1].copy()),
+        dict(colidx=np.where(np.arange(w.nnz) == 5, w.n, w.colidx).astype(np.int32)),
+        dict(colidx=np.where(np.arange(w.nnz) == 1, w.colidx[0], w.colidx).astype(np.int32)),
+    ]
+    for kw in bad:
+        args = dict(rowptr=w.rowptr, colidx=w.colidx, vals=w.vals, b=8)
+        args.update(kw)
+        with pytest.raises(binding.ArrowError) as ei:
+            binding.arrow_decompose(**args)
+        assert ei.value.code == binding.ARROW_EINVAL and binding.arrow_last_error()
+    h = binding.arrow_decompose(w.rowptr, w.colidx, w.vals, 8)
+    try:
+        # compute calls before upload / workspace are refused on the host, no GPU involved
+        with pytest.raises(binding.ArrowError) as ei:
+            binding.arrow_spmm(h, 4096, 8192, 4)
+        assert ei.value.code == binding.ARROW_ENOTREADY
+        with pytest.raises(binding.ArrowError) as ei:
+            binding.arrow_spmm(h, 4096, 8192, 0)
+        assert ei.value.code == binding.ARROW_EINVAL
+        with pytest.raises(binding.ArrowError) as ei:
+            binding.arrow_spmm_iter(h, 4096, 4, -1)
+        assert ei.value.code == binding.ARROW_EINVAL
+        with pytest.raises(binding.ArrowError):
+            binding.arrow_level_info(h, 99)
+        with pytest.raises(binding.ArrowError):
+            binding.arrow_set_option(h, "no_such_option", 1)
+        with pytest.raises(binding.ArrowError) as ei:
+            binding.arrow_upload(h, 4096, 1, 0)
+        assert ei.value.code == binding.ARROW_ETOOSMALL
+        assert binding.arrow_device_bytes(h) > 0 and binding.arrow_workspace_bytes(h, 4) > 0
+    finally:
+        binding.arrow_destroy(h)
+    binding.arrow_destroy(None)                          # NULL is ignored
+
+
+def test_library_exports_every_declared_symbol():
+    import re
+    header = open(os.path.join(os.path.dirname(_build.REPO_DIR + "/x"), "include", "arrow.h")).read()
+    declared = set(re.findall(r"\b(arrow_[a-z_]+)\s*\(", header))
+    declared -= {"arrow_handle"}
+    L = binding.lib()
+    for name in sorted(declared):
+        assert hasattr(L, name), f"{name} is declared in arrow.h but not exported"
+    assert declared == set(binding.EXPORTED)

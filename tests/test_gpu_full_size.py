@@ -1,0 +1,82 @@
+"""Parity at the full sizes of the named workloads, in the launch configuration ``bench.py``
+times (default options).  Where the whole fp64 product is too large to hold, sampled rows are
+checked: every output row is an independent sum, so the oracle computes any row on its own."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2307_05740_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible")
+    return torch
+
+
+def check(Y, Yref, B, scale=1.0):
+    err = np.abs(np.asarray(Y, np.float64) - Yref)
+    assert np.all(err <= scale * TOL * B), f"max err/bound = {np.max(err / np.maximum(B, 1e-300)):.3e}"
+    assert np.all(np.asarray(Y)[B == 0] == 0)
+
+
+def test_config1_grid_1024_full(torch):
+    w = synth.make_config(1)
+    X = w.make_x()
+    op = binding.ArrowSpMM(w.rowptr, w.colidx, w.vals, w.b)
+    assert op.info["levels"] == 1                       # one arrow matrix, as the workload states
+    Y = op.spmm(torch.from_numpy(X).cuda()).cpu().numpy()
+    Yref, B = oracle.spmm(w.rowptr, w.colidx, w.vals, X)
+    check(Y, Yref, B)
+    op.close()
+
+
+def test_config2_rmat_s20_cubed_full(torch):
+    w = synth.make_config(2)
+    X = w.make_x()
+    op = binding.ArrowSpMM(w.rowptr, w.colidx, w.vals, w.b)
+    Xd = torch.from_numpy(X).cuda()
+    op.spmm_iter(Xd, w.l)
+    Xl, El = oracle.spmm_iter(w.rowptr, w.colidx, w.vals, X, w.l)
+    check(Xd.cpu().numpy(), Xl, El, scale=w.l)
+    op.close()
+
+
+def test_config3_rmat_s23_k128_sampled_rows(torch):
+    print("generating R-MAT scale 23 ...", flush=True)
+    w = synth.make_config(3)
+    print(f"decomposing n={w.n} nnz={w.nnz} ...", flush=True)
+    op = binding.ArrowSpMM(w.rowptr, w.colidx, w.vals, w.b)
+    X = w.make_x()
+    print(f"levels={op.info['levels']}; product ...", flush=True)
+    Xd = torch.from_numpy(X).cuda()
+    Yd = torch.full_like(Xd, float("nan"))
+    op.spmm(Xd, Yd)
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(Yd).any())              # every row of Y was written
+    deg = np.diff(w.rowptr)
+    rng = np.random.default_rng(23)
+    rows = np.unique(np.concatenate([
+        np.argsort(deg)[-48:],                          # the heaviest hub rows (split + reduced)
+        np.flatnonzero(deg == 0)[:16],                  # empty rows
+        rng.integers(0, w.n, 4096),                     # uniform sample
+        np.arange(0, w.n, w.n // 512)])).astype(np.int64)
+    print(f"oracle on {len(rows)} sampled rows ...", flush=True)
+    Yref, B = oracle.spmm(w.rowptr, w.colidx, w.vals, X, rows=rows)
+    Ys = Yd[torch.from_numpy(rows).cuda()].cpu().numpy()
+    check(Ys, Yref, B)
+    # properties that hold at any size: column sums  1^T Y = (1^T A) X  in fp64
+    colsum = torch.zeros(w.k, dtype=torch.float64, device="cuda")
+    for s in range(0, w.n, 1 << 20):
+        colsum += Yd[s:s + (1 << 20)].double().sum(0)
+    ata = np.zeros(w.n, np.float64)
+    np.add.at(ata, w.colidx, w.vals.astype(np.float64))          # 1^T A
+    want = ata @ X.astype(np.float64)
+    scale = np.abs(ata) @ np.abs(X.astype(np.float64))
+    assert np.all(np.abs(colsum.cpu().numpy() - want) <= 1e-5 * scale)
+    op.close()

@@ -1,0 +1,239 @@
+"""GPU parity: the HIP path, called through the C-ABI, against the fp64 CPU oracle on the same
+seeded inputs.  Bar (elementwise): |Y - Yref| <= 1e-5 * (|A|.|X|), times l for chained products,
+and exactly 0 where the bound is 0 (empty rows)."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import arrow_checks
+from paper_2307_05740_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: the parity tests need a real MI355X")
+    if not os.path.exists(binding.LIB_PATH):
+        pytest.fail("libarrow.so is not built")
+    return torch
+
+
+def assert_within(Y, Yref, B, scale=1.0):
+    Y = np.asarray(Y, dtype=np.float64)
+    err = np.abs(Y - Yref)
+    lim = scale * TOL * B
+    bad = err > lim
+    if bad.any():
+        i = np.unravel_index(np.argmax(err - lim), err.shape)
+        raise AssertionError(f"{bad.sum()} of {bad.size} elements outside the bound; worst at {i}: "
+                             f"got {Y[i]!r} want {Yref[i]!r} bound {lim[i]!r}")
+    assert np.all(Y[B == 0] == 0)
+    # the bound is not vacuous: typical error is far below it
+    nz = B > 0
+    if nz.any():
+        assert np.median(err[nz] / B[nz]) < 1e-6
+
+
+def run_product(torch, w_or_csr, b, X, **opts):
+    rowptr, colidx, vals = w_or_csr
+    op = binding.ArrowSpMM(rowptr, colidx, vals, b)
+    for name, v in opts.items():
+        binding.arrow_set_option(op.h, name, v)
+    Xd = torch.from_numpy(X).cuda()
+    Yd = torch.full_like(Xd, float("nan"))          # every element must be written
+    op.spmm(Xd, Yd)
+    torch.cuda.synchronize()
+    Y = Yd.cpu().numpy()
+    return op, Xd, Y
+
+
+def csr_of(w):
+    return (w.rowptr, w.colidx, w.vals)
+
+
+def test_config0_rmat_s12_k16(torch):
+    w = synth.make_config(0)
+    X = w.make_x()
+    op, Xd, Y = run_product(torch, csr_of(w), w.b, X)
+    Yref, B = oracle.spmm(*csr_of(w), X)
+    assert_within(Y, Yref, B)
+    assert op.info["levels"] >= 1
+    # run-to-run bitwise reproducibility (no floating-point atomics)
+    Y2 = op.spmm(Xd).cpu().numpy()
+    assert np.array_equal(Y.view(np.uint32), Y2.view(np.uint32))
+    op.close()
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 6, 7, 12, 16, 20, 33, 64, 100, 128, 130, 200, 256, 260, 516])
+def test_all_column_counts(torch, k):
+    w = synth.make_config(0, shrink=1)              # n = 2048, b = 256
+    X = synth.normal_matrix(w.n, k, seed=100 + k)
+    op, _, Y = run_product(torch, csr_of(w), w.b, X)
+    Yref, B = oracle.spmm(*csr_of(w), X)
+    assert_within(Y, Yref, B)
+    op.close()
+
+
+@pytest.mark.parametrize("opts", [dict(kc=16), dict(kc=32), dict(kc=64), dict(xcd_remap=0),
+                                  dict(kc=32, xcd_remap=0)])
+def test_launch_options(torch, opts):
+    w = synth.make_config(3, shrink=9)              # R-MAT scale 14, k = 128, b = 512
+    X = w.make_x()
+    op, _, Y = run_product(torch, csr_of(w), w.b, X, **opts)
+    Yref, B = oracle.spmm(*csr_of(w), X)
+    assert_within(Y, Yref, B)
+    op.close()
+
+
+@pytest.mark.parametrize("b", [1, 5, 64, 1000, 2048, 5000])
+def test_block_widths(torch, b):
+    w = synth.make_config(0, shrink=1)
+    X = synth.normal_matrix(w.n, 24, seed=7)
+    op, _, Y = run_product(torch, csr_of(w), b, X)
+    Yref, B = oracle.spmm(*csr_of(w), X)
+    assert_within(Y, Yref, B)
+    op.close()
+
+
+def test_pack_options_short_and_chunk(torch, monkeypatch):
+    w = synth.make_config(0)
+    X = synth.normal_matrix(w.n, 32, seed=8)
+    Yref, B = oracle.spmm(*csr_of(w), X)
+    for short_max, chunk in ((0, 7), (4, 64), (64, 100000), (1000000, 512)):
+        monkeypatch.setenv("ARROW_SHORT_MAX", str(short_max))
+        monkeypatch.setenv("ARROW_CHUNK_NNZ", str(chunk))
+        op, _, Y = run_product(torch, csr_of(w), w.b, X)
+        assert_within(Y, Yref, B)
+        op.close()
+
+
+def test_grid_one_level(torch):
+    w = synth.make_config(1, shrink=4)              # 256 x 256 grid, k = 32, b = 4096
+    X = w.make_x()
+    op, _, Y = run_product(torch, csr_of(w), w.b, X)
+    assert op.info["levels"] == 1
+    Yref, B = oracle.spmm(*csr_of(w), X)
+    assert_within(Y, Yref, B)
+    # closed form: the operator applied to ones is 4 - (number of neighbours), exactly
+    ones = np.ones((w.n, 4), np.float32)
+    Y1 = op.spmm(torch.from_numpy(ones).cuda()).cpu().numpy().reshape(256, 256, 4)
+    assert np.all(Y1[1:-1, 1:-1] == 0) and np.all(Y1[0, 1:-1] == 1) and Y1[0, 0, 0] == 2
+    op.close()
+
+
+def test_hub_row_is_split_and_reduced(torch):
+    # one vertex adjacent to everything: its row has n entries -> many chunks + reduction
+    n, k, b = 40000, 20, 1024
+    rows = np.concatenate([np.zeros(n, np.int64), np.arange(1, n)])
+    cols = np.concatenate([np.arange(n), np.zeros(n - 1, np.int64)])
+    order = np.lexsort((cols, rows))
+    rows, cols = rows[order], cols[order]
+    rowptr = np.zeros(n + 1, np.int64)
+    np.add.at(rowptr, rows + 1, 1)
+    rowptr = np.cumsum(rowptr)
+    colidx = cols.astype(np.int32)
+    vals = synth.fill_uniform(rowptr, colidx, seed=5)
+    X = synth.normal_matrix(n, k, seed=6)
+    op, _, Y = run_product(torch, (rowptr, colidx, vals), b, X)
+    assert op.levels()[0]["split_rows"] >= 1
+    Yref, B = oracle.spmm(rowptr, colidx, vals, X)
+    assert_within(Y, Yref, B)
+    op.close()
+
+
+def test_special_operands_bitwise(torch):
+    rng = np.random.default_rng(3)
+    n, k = 3000, 12
+    X = rng.standard_normal((n, k)).astype(np.float32)
+    rp = np.arange(n + 1, dtype=np.int64)
+    perm = rng.permutation(n).astype(np.int32)
+    d = rng.uniform(-2, 2, n).astype(np.float32)
+    for colidx, vals, want in ((np.arange(n, dtype=np.int32), np.ones(n, np.float32), X),
+                               (perm, np.ones(n, np.float32), X[perm]),
+                               (np.arange(n, dtype=np.int32), d, d[:, None] * X)):
+        op, _, Y = run_product(torch, (rp, colidx, vals), 256, X)
+        assert np.array_equal(Y, want.astype(np.float32))     # one term per row: no rounding freedom
+        op.close()
+    # empty operand: Y is all zeros
+    op, _, Y = run_product(torch, (np.zeros(n + 1, np.int64), np.zeros(0, np.int32), np.zeros(0, np.float32)),
+                           256, X)
+    assert np.all(Y == 0)
+    op.close()
+
+
+def test_gather_kernel_matches_exported_permutation(torch):
+    w = synth.make_config(2, shrink=8)
+    X = w.make_x()
+    op = binding.ArrowSpMM(*csr_of(w), w.b)
+    Xd = torch.from_numpy(X).cuda()
+    for level in range(op.info["levels"]):
+        perm = binding.arrow_export_level(op.h, level)[0]
+        Xp = op.gather(level, Xd).cpu().numpy()
+        assert np.array_equal(Xp, X[perm])
+    op.close()
+
+
+@pytest.mark.parametrize("idx,shrink", [(2, 6), (4, 8)])
+def test_chained_products(torch, idx, shrink):
+    w = synth.make_config(idx, shrink=shrink)       # row-normalised operands, A^3 / A^5
+    X = w.make_x()
+    op = binding.ArrowSpMM(*csr_of(w), w.b)
+    for l in (0, 1, 2, w.l):
+        Xd = torch.from_numpy(X).cuda()
+        op.spmm_iter(Xd, l)
+        torch.cuda.synchronize()
+        Xl, El = oracle.spmm_iter(*csr_of(w), X, l)
+        if l == 0:
+            assert np.array_equal(Xd.cpu().numpy(), X)
+        else:
+            assert_within(Xd.cpu().numpy(), Xl, El, scale=l)
+    op.close()
+
+
+def test_grid_eigenvector_powers(torch):
+    N = 64
+    rp, ci = synth.grid5_pattern(N)
+    vals = synth.fill_grid5(rp, ci)
+    xs = np.arange(1, N + 1)
+    v = np.outer(np.sin(np.pi * 3 * xs / (N + 1)), np.sin(np.pi * 2 * xs / (N + 1))).reshape(-1, 1)
+    lam = 4 - 2 * np.cos(np.pi * 2 / (N + 1)) - 2 * np.cos(np.pi * 3 / (N + 1))
+    X = np.repeat(v, 4, axis=1).astype(np.float32)
+    op = binding.ArrowSpMM(rp, ci, vals, 1024)
+    Xd = torch.from_numpy(X).cuda()
+    op.spmm_iter(Xd, 4)
+    got = Xd.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - lam ** 4 * X) <= 4 * TOL * 8.0 ** 4 * np.abs(X).max())
+    op.close()
+
+
+def test_errors_on_device(torch):
+    w = synth.make_config(0, shrink=3)
+    op = binding.ArrowSpMM(*csr_of(w), w.b)
+    Xd = torch.zeros((w.n, 8), device="cuda")
+    op.spmm(Xd)
+    with pytest.raises(binding.ArrowError) as ei:                     # in place is refused
+        binding.arrow_spmm(op.h, Xd.data_ptr(), Xd.data_ptr(), 8, 0)
+    assert ei.value.code == binding.ARROW_EINVAL
+    with pytest.raises(binding.ArrowError) as ei:                     # workspace bound for k = 8 only
+        binding.arrow_spmm_iter(op.h, Xd.data_ptr(), 64, 2, 0)
+    assert ei.value.code == binding.ARROW_ETOOSMALL
+    op.close()
+
+
+def test_exported_levels_match_what_the_gpu_ran(torch):
+    """Invariants on the very handle the GPU product used (bit-exact reassembly, arrow shape)."""
+    w = synth.make_config(3, shrink=8)              # R-MAT scale 15, b = 1024
+    X = w.make_x()
+    op, _, Y = run_product(torch, csr_of(w), w.b, X)
+    levels = [binding.arrow_export_level(op.h, i) for i in range(op.info["levels"])]
+    arrow_checks.check_decomposition(w.n, w.rowptr, w.colidx, w.vals, w.b, levels)
+    Yref, B = oracle.spmm(*csr_of(w), X)
+    assert_within(Y, Yref, B)
+    op.close()
