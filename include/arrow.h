@@ -85,6 +85,9 @@ typedef struct arrow_level_info_t {
   int64_t nnz_chunks;   /* entries held by the chunk list                        */
   int64_t x_rows_rows;  /* distinct rows of X the row list reads                 */
   int64_t x_rows_chunks;/* distinct rows of X the chunk list reads               */
+  int64_t window_tiles; /* diagonal-block tiles run with their X window in LDS   */
+  int64_t window_rows;  /* rows those tiles cover                                */
+  int64_t nnz_window;   /* entries of those rows                                 */
   int32_t blocks;       /* ceil(n_i / b)                                         */
   int32_t separator_rule; /* 1 if block separators were promoted into the head   */
 } arrow_level_info_t;
@@ -94,9 +97,10 @@ typedef struct arrow_profile_t {
   float rows_ms;    /* lane-group-per-row kernel (first block column + diagonal blocks, short head rows) */
   float chunks_ms;  /* wavefront-per-chunk kernel (head rows and other long rows)                         */
   float reduce_ms;  /* cross-chunk reduction + scatter                                                    */
-  float window_ms;  /* diagonal blocks with the X window staged in LDS                                    */
+  float stage_ms;  /* gather of the head rows X_0 into the contiguous staging buffer                      */
+  float window_ms;  /* diagonal-block tiles with the X window staged in LDS                               */
   float total_ms;   /* first launch to last launch of the product                                         */
-  int32_t rows_launches, chunks_launches, reduce_launches, window_launches; /* launches per class (one per level that has such work) */
+  int32_t rows_launches, chunks_launches, reduce_launches, stage_launches, window_launches; /* launches per class (one per level that has such work) */
 } arrow_profile_t;
 
 /*
@@ -173,13 +177,26 @@ int arrow_export_level(const arrow_handle *h, int32_t level, int32_t *perm,
 
 /*
  * Launch-time tunables, by name:
- *   "kc"        columns per pass (0 = automatic: min(k, 64 lanes x 4 columns)); a smaller slice
- *               shrinks the working set of X rows per pass and re-reads the entries k/kc times
- *   "xcd_remap" 1 (default): consecutive work items run on the same accelerator die
+ *   "kc"        columns per pass of the chunk kernel; a smaller slice shrinks the working set of
+ *               X rows per pass and re-reads the entries k/kc times.  0 = automatic: 64 when the
+ *               head is staged and k > 64, the whole row (up to 256 columns) otherwise
+ *   "l2_resident_bytes"  share of one die's 4 MiB L2 that a resident slice of the staged head
+ *               may take when kc is chosen automatically (default 2 MiB)
  * Pack-time choices are read from the environment by arrow_decompose: ARROW_SHORT_MAX (rows
  * with at most this many entries are handled one per lane group, default 16), ARROW_CHUNK_NNZ
- * (entries per wavefront chunk, default 512), ARROW_SEPARATORS and ARROW_BFS_TAIL (0 disables
- * the separator rule / the breadth-first arrangement of later levels).
+ * (most entries per wavefront chunk, default 256), ARROW_WINDOW_ROWS (long rows are cut at
+ * multiples of this many column positions and their chunks run window by window, default 4096,
+ * 0 = plain row-major chunks), ARROW_CHUNK_MIN (windows of a row are merged until a chunk
+ * holds this many entries, default 64), ARROW_CLASSES (column classes of the die queues, a
+ * multiple of 8, default 0 = none), ARROW_CLASS_GRAN (column positions dealt to a class at a time,
+ * default 512), ARROW_CLASS_MIN (a row is split by class when it holds classes x this many
+ * entries, default 32), ARROW_STAGE_HEAD (1: the head rows of level 0 are gathered into a
+ * contiguous buffer before the product), ARROW_WINDOW_SPAN (widest column span of a diagonal-block tile whose
+ * window of P_i X is staged in LDS, default 2048, at most 4096, 0 = no such tiles),
+ * ARROW_WINDOW_TILE_ROWS (most rows per tile, default 1024), ARROW_WINDOW_REUSE_X10 (a tile is
+ * kept when its diagonal-block entries number at least this / 10 times its span, default 20),
+ * ARROW_SEPARATORS and ARROW_BFS_TAIL (0 disables the separator rule / the breadth-first
+ * arrangement of later levels).
  * Errors: EINVAL (unknown name, value out of range).
  */
 int arrow_set_option(arrow_handle *h, const char *name, int64_t value);
@@ -191,6 +208,9 @@ int arrow_set_option(arrow_handle *h, const char *name, int64_t value);
  */
 int arrow_set_profiling(arrow_handle *h, int32_t enabled);
 int arrow_get_profile(arrow_handle *h, arrow_profile_t *out);
+/* Same, restricted to the launches of one level (level < 0: all levels; total_ms always spans
+ * the whole product). */
+int arrow_get_level_profile(arrow_handle *h, int32_t level, arrow_profile_t *out);
 
 /* Thread-local text of the last error ("" if none). Never NULL. */
 const char *arrow_last_error(void);

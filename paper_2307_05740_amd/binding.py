@@ -24,7 +24,7 @@ EXPORTED = [
     "arrow_decompose", "arrow_device_bytes", "arrow_upload", "arrow_workspace_bytes",
     "arrow_set_workspace", "arrow_spmm", "arrow_spmm_iter", "arrow_gather", "arrow_info",
     "arrow_level_info", "arrow_export_level", "arrow_set_option", "arrow_set_profiling",
-    "arrow_get_profile", "arrow_last_error", "arrow_destroy",
+    "arrow_get_profile", "arrow_get_level_profile", "arrow_last_error", "arrow_destroy",
 ]
 
 
@@ -44,15 +44,16 @@ class arrow_level_info_t(ctypes.Structure):
     _fields_ = [(name, ctypes.c_int64) for name in
                 ("n_i", "nnz", "nnz_head_head", "nnz_head_row", "nnz_head_col", "nnz_diag",
                  "short_rows", "chunks", "split_rows", "partials", "nnz_rows", "nnz_chunks",
-                 "x_rows_rows", "x_rows_chunks")] + \
+                 "x_rows_rows", "x_rows_chunks", "window_tiles", "window_rows", "nnz_window")] + \
                [("blocks", ctypes.c_int32), ("separator_rule", ctypes.c_int32)]
 
 
 class arrow_profile_t(ctypes.Structure):
     _fields_ = [(name, ctypes.c_float) for name in
-                ("rows_ms", "chunks_ms", "reduce_ms", "window_ms", "total_ms")] + \
+                ("rows_ms", "chunks_ms", "reduce_ms", "stage_ms", "window_ms", "total_ms")] + \
                [(name, ctypes.c_int32) for name in
-                ("rows_launches", "chunks_launches", "reduce_launches", "window_launches")]
+                ("rows_launches", "chunks_launches", "reduce_launches", "stage_launches",
+                 "window_launches")]
 
 
 def lib():
@@ -93,6 +94,8 @@ def lib():
     L.arrow_set_profiling.argtypes = [vp, i32]
     L.arrow_get_profile.restype = ctypes.c_int
     L.arrow_get_profile.argtypes = [vp, ctypes.POINTER(arrow_profile_t)]
+    L.arrow_get_level_profile.restype = ctypes.c_int
+    L.arrow_get_level_profile.argtypes = [vp, i32, ctypes.POINTER(arrow_profile_t)]
     L.arrow_last_error.restype = ctypes.c_char_p
     L.arrow_last_error.argtypes = []
     L.arrow_destroy.restype = None
@@ -186,6 +189,12 @@ def arrow_set_profiling(h: int, enabled: bool) -> None:
 def arrow_get_profile(h: int) -> dict:
     out = arrow_profile_t()
     _check(lib().arrow_get_profile(h, ctypes.byref(out)))
+    return {f: getattr(out, f) for f, _ in out._fields_}
+
+
+def arrow_get_level_profile(h: int, level: int) -> dict:
+    out = arrow_profile_t()
+    _check(lib().arrow_get_level_profile(h, level, ctypes.byref(out)))
     return {f: getattr(out, f) for f, _ in out._fields_}
 
 

@@ -42,10 +42,11 @@ int64_t env_int(const char* name, int64_t dflt) {
 constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
-enum KernelClass { kRows = 0, kChunks = 1, kReduce = 2, kWindow = 3, kClasses = 4 };
+enum KernelClass { kRows = 0, kChunks = 1, kReduce = 2, kStage = 3, kWindow = 4, kClasses = 5 };
 
 struct Span {
   int cls;
+  int level;
   hipEvent_t a, b;
 };
 
@@ -71,8 +72,12 @@ struct arrow_handle {
 
 namespace {
 
+// workspace layout: [partial vectors][staged head rows][n x k buffer of the chained products]
 size_t partial_bytes(const arrow_handle* h, int32_t k) {
   return align_up((size_t)h->img.max_partials * (size_t)k * sizeof(float));
+}
+size_t stage_bytes(const arrow_handle* h, int32_t k) {
+  return align_up((size_t)h->img.max_stage_rows * (size_t)k * sizeof(float));
 }
 
 template <typename T>
@@ -85,15 +90,16 @@ struct Scoped {
   arrow_handle* h;
   hipStream_t s;
   Span* sp = nullptr;
-  Scoped(arrow_handle* h_, int cls, hipStream_t s_) : h(h_), s(s_) {
+  Scoped(arrow_handle* h_, int cls, int level, hipStream_t s_) : h(h_), s(s_) {
     if (!h->profiling) return;
     if (h->spans_used == h->spans.size()) {
-      Span n{cls, nullptr, nullptr};
+      Span n{cls, level, nullptr, nullptr};
       if (hipEventCreate(&n.a) != hipSuccess || hipEventCreate(&n.b) != hipSuccess) return;
       h->spans.push_back(n);
     }
     sp = &h->spans[h->spans_used++];
     sp->cls = cls;
+    sp->level = level;
     (void)hipEventRecord(sp->a, s);
   }
   ~Scoped() {
@@ -109,24 +115,55 @@ int check_hip(int rc, const char* what) {
 // one product, src -> dst (device, n x k), all levels in stream order
 int product(arrow_handle* h, const float* X, float* Y, int32_t k, hipStream_t stream) {
   float* partials = reinterpret_cast<float*>(h->ws);
+  float* stage = reinterpret_cast<float*>(h->ws + partial_bytes(h, k));
   for (size_t li = 0; li < h->img.levels.size(); ++li) {
     const arrow::LevelImage& im = h->img.levels[li];
     const bool acc = li > 0;
     const arrow::Entry* ent = at<arrow::Entry>(h, im.off_entries);
+    const float* Xh = X;
+    arrow::LaunchTuning tune = h->tuning;
+    if (im.staged) {
+      // the first-block-column window X_0 = (P_i X)[0:b], made contiguous once per product
+      Scoped sc(h, kStage, (int)li, stream);
+      int rc = arrow::launch_gather(at<int32_t>(h, im.off_stage_perm), im.n_stage, X, stage, k, stream);
+      if (rc) return check_hip(rc, "head staging launch");
+      Xh = stage;
+    }
+    if (tune.kc == 0) {
+      if (im.staged && im.classes > 0) {
+        // column slice such that one class of the staged head (one die's share) stays in its 4 MiB L2
+        int64_t kc = 256;
+        while (kc > 16 && im.stage_class_rows * kc * 4 > tune.l2_resident_bytes) kc >>= 1;
+        if (kc < k) tune.kc = (int32_t)kc;
+      } else if (im.staged && k > 64) {
+        // window-ordered chunks: 64-column passes halve the bytes of a column window, which the
+        // L2 hit rate of the head rows gains more from than the second pass over the entries costs
+        tune.kc = 64;
+      }
+    }
     if (im.n_chunks > 0) {
-      Scoped sc(h, kChunks, stream);
-      int rc = arrow::launch_chunks(at<uint32_t>(h, im.off_chunk_ptr), at<int32_t>(h, im.off_chunk_dst),
-                                    ent, im.n_chunks, X, Y, partials, k, acc, h->tuning, stream);
+      Scoped sc(h, kChunks, (int)li, stream);
+      int rc = arrow::launch_chunks(at<uint32_t>(h, im.off_chunk_ptr), at<uint32_t>(h, im.off_chunk_mid),
+                                    at<int32_t>(h, im.off_chunk_dst), ent, im.n_chunks, X, h->n, Xh, Y,
+                                    partials, k, acc, tune, stream);
       if (rc) return check_hip(rc, "chunks kernel launch");
     }
     if (im.n_rows > 0) {
-      Scoped sc(h, kRows, stream);
+      Scoped sc(h, kRows, (int)li, stream);
       int rc = arrow::launch_rows(at<uint32_t>(h, im.off_rows_ptr), at<int32_t>(h, im.off_rows_y), ent,
-                                  im.n_rows, X, Y, k, acc, h->tuning, stream);
+                                  im.n_rows, X, h->n, Y, k, acc, h->tuning, stream);
       if (rc) return check_hip(rc, "rows kernel launch");
     }
+    if (im.n_wtiles > 0) {
+      Scoped sc(h, kWindow, (int)li, stream);
+      int rc = arrow::launch_window(at<arrow::WindowTile>(h, im.off_wtiles), im.n_wtiles,
+                                    h->img.max_window_span, at<uint32_t>(h, im.off_wrow_ptr),
+                                    at<uint32_t>(h, im.off_wrow_mid), at<int32_t>(h, im.off_wrow_y), ent,
+                                    at<int32_t>(h, im.off_perm), X, Y, k, acc, stream);
+      if (rc) return check_hip(rc, "window kernel launch");
+    }
     if (im.n_split > 0) {
-      Scoped sc(h, kReduce, stream);
+      Scoped sc(h, kReduce, (int)li, stream);
       int rc = arrow::launch_reduce(at<uint32_t>(h, im.off_split_ptr), at<int32_t>(h, im.off_split_y),
                                     im.n_split, partials, Y, k, acc, stream);
       if (rc) return check_hip(rc, "reduce kernel launch");
@@ -140,7 +177,7 @@ int ready(const arrow_handle* h, int32_t k, bool need_iter_buffer) {
   if (k < 1) return fail(ARROW_EINVAL, "k must be >= 1 (got %d)", k);
   if (!h->dev) return fail(ARROW_ENOTREADY, "arrow_upload has not been called");
   if (!h->ws) return fail(ARROW_ENOTREADY, "arrow_set_workspace has not been called");
-  size_t need = partial_bytes(h, k);
+  size_t need = partial_bytes(h, k) + stage_bytes(h, k);
   if (need_iter_buffer) need += (size_t)h->n * (size_t)k * sizeof(float);
   if (h->ws_bytes < need)
     return fail(ARROW_ETOOSMALL, "workspace holds %zu bytes, k = %d needs %zu", h->ws_bytes, k, need);
@@ -190,8 +227,18 @@ int arrow_decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, con
   dopt.bfs_tail = env_int("ARROW_BFS_TAIL", 1) != 0;
   h->pack.short_max = (int32_t)env_int("ARROW_SHORT_MAX", h->pack.short_max);
   h->pack.chunk_nnz = (int32_t)env_int("ARROW_CHUNK_NNZ", h->pack.chunk_nnz);
+  h->pack.chunk_min = (int32_t)env_int("ARROW_CHUNK_MIN", h->pack.chunk_min);
+  h->pack.window_rows = (int32_t)env_int("ARROW_WINDOW_ROWS", h->pack.window_rows);
+  h->pack.classes = (int32_t)env_int("ARROW_CLASSES", h->pack.classes);
+  h->pack.class_gran = (int32_t)env_int("ARROW_CLASS_GRAN", h->pack.class_gran);
+  h->pack.class_min = (int32_t)env_int("ARROW_CLASS_MIN", h->pack.class_min);
+  h->pack.stage_head = (int32_t)env_int("ARROW_STAGE_HEAD", h->pack.stage_head);
+  h->pack.window_span = (int32_t)env_int("ARROW_WINDOW_SPAN", h->pack.window_span);
+  if (h->pack.window_span > 4096) h->pack.window_span = 4096;   // 4096 positions x 4 columns x 4 B = 64 KiB of LDS
+  h->pack.window_tile_rows = (int32_t)env_int("ARROW_WINDOW_TILE_ROWS", h->pack.window_tile_rows);
+  h->pack.window_reuse = (double)env_int("ARROW_WINDOW_REUSE_X10", (int64_t)(h->pack.window_reuse * 10)) / 10.0;
+  h->tuning.l2_resident_bytes = env_int("ARROW_L2_RESIDENT_BYTES", h->tuning.l2_resident_bytes);
   h->tuning.kc = (int32_t)env_int("ARROW_KC", 0);
-  h->tuning.xcd_remap = (int32_t)env_int("ARROW_XCD_REMAP", 1);
   std::string err;
   int rc;
   try {
@@ -230,7 +277,7 @@ int arrow_upload(arrow_handle* h, void* dev_buf, size_t bytes, void* stream) {
 
 size_t arrow_workspace_bytes(const arrow_handle* h, int32_t k) {
   if (!h || k < 1) return 0;
-  return partial_bytes(h, k) + align_up((size_t)h->n * (size_t)k * sizeof(float));
+  return partial_bytes(h, k) + stage_bytes(h, k) + align_up((size_t)h->n * (size_t)k * sizeof(float));
 }
 
 int arrow_set_workspace(arrow_handle* h, void* dev_ws, size_t bytes) {
@@ -260,7 +307,7 @@ int arrow_spmm_iter(arrow_handle* h, float* X, int32_t k, int32_t l, void* strea
   if ((uintptr_t)X % 16) return fail(ARROW_EINVAL, "X must be 16-byte aligned");
   if (l == 0) return ARROW_OK;
   h->spans_used = 0;
-  float* tmp = reinterpret_cast<float*>(h->ws + partial_bytes(h, k));
+  float* tmp = reinterpret_cast<float*>(h->ws + partial_bytes(h, k) + stage_bytes(h, k));
   float* src = X;
   float* dst = tmp;
   for (int32_t t = 0; t < l; ++t) {
@@ -305,9 +352,10 @@ int arrow_level_info(const arrow_handle* h, int32_t level, arrow_level_info_t* o
   out->nnz = L.rowptr[L.n_i];
   out->nnz_head_head = L.nnz_head_head; out->nnz_head_row = L.nnz_head_row;
   out->nnz_head_col = L.nnz_head_col; out->nnz_diag = L.nnz_diag;
-  out->short_rows = im.n_rows; out->chunks = im.n_chunks; out->split_rows = im.n_split;
+  out->short_rows = im.n_rows; out->chunks = im.n_real_chunks; out->split_rows = im.n_split;
   out->partials = im.n_partials; out->nnz_rows = im.nnz_rows; out->nnz_chunks = im.nnz_chunks;
   out->x_rows_rows = im.x_rows_rows; out->x_rows_chunks = im.x_rows_chunks;
+  out->window_tiles = im.n_wtiles; out->window_rows = im.n_wrows; out->nnz_window = im.nnz_w;
   out->blocks = (int32_t)((L.n_i + h->b - 1) / h->b);
   out->separator_rule = L.separator_rule ? 1 : 0;
   return ARROW_OK;
@@ -335,8 +383,9 @@ int arrow_set_option(arrow_handle* h, const char* name, int64_t value) {
   if (!std::strcmp(name, "kc")) {
     if (value < 0 || value > 256) return fail(ARROW_EINVAL, "kc must be in [0, 256]");
     h->tuning.kc = (int32_t)value;
-  } else if (!std::strcmp(name, "xcd_remap")) {
-    h->tuning.xcd_remap = value ? 1 : 0;
+  } else if (!std::strcmp(name, "l2_resident_bytes")) {
+    if (value < 0) return fail(ARROW_EINVAL, "l2_resident_bytes must be >= 0");
+    h->tuning.l2_resident_bytes = value;
   } else {
     return fail(ARROW_EINVAL, "unknown option '%s'", name);
   }
@@ -350,16 +399,21 @@ int arrow_set_profiling(arrow_handle* h, int32_t enabled) {
   return ARROW_OK;
 }
 
-int arrow_get_profile(arrow_handle* h, arrow_profile_t* out) {
+int arrow_get_profile(arrow_handle* h, arrow_profile_t* out) { return arrow_get_level_profile(h, -1, out); }
+
+int arrow_get_level_profile(arrow_handle* h, int32_t level, arrow_profile_t* out) {
   if (!h || !out) return fail(ARROW_EINVAL, "NULL argument");
+  if (level >= (int32_t)h->img.levels.size()) return fail(ARROW_EINVAL, "no level %d", level);
   std::memset(out, 0, sizeof *out);
   if (h->spans_used == 0) return fail(ARROW_ENOTREADY, "no profiled product has run");
   hipError_t e = hipEventSynchronize(h->spans[h->spans_used - 1].b);
   if (e != hipSuccess) return check_hip((int)e, "event synchronize");
-  float* slot[kClasses] = {&out->rows_ms, &out->chunks_ms, &out->reduce_ms, &out->window_ms};
+  float* slot[kClasses] = {&out->rows_ms, &out->chunks_ms, &out->reduce_ms, &out->stage_ms,
+                           &out->window_ms};
   int32_t* count[kClasses] = {&out->rows_launches, &out->chunks_launches, &out->reduce_launches,
-                              &out->window_launches};
+                              &out->stage_launches, &out->window_launches};
   for (size_t i = 0; i < h->spans_used; ++i) {
+    if (level >= 0 && h->spans[i].level != level) continue;
     float ms = 0.f;
     e = hipEventElapsedTime(&ms, h->spans[i].a, h->spans[i].b);
     if (e != hipSuccess) return check_hip((int)e, "event elapsed time");

@@ -36,23 +36,33 @@ int decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const flo
 // Device image.  All offsets are byte offsets from the image base, 256-aligned.
 // ---------------------------------------------------------------------------
 
-// Entry of a work list: the X row to read (perm already applied) and the value.
+// Entry of a work list: the row to read (perm already applied, or a staged head row) and the value.
 struct Entry {
   int32_t xrow;
   float val;
 };
 
+constexpr int kDies = 8;             // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
+constexpr int kChunksPerGroup = 4;   // wavefronts (chunks) per workgroup of the chunk kernel
+
 struct LevelImage {
   int64_t n_i = 0;
   // permutation (int32 n_i)
   size_t off_perm = 0;
+  // staged head: rows of X gathered into a contiguous buffer before the level runs
+  bool staged = false;
+  int64_t n_stage = 0;          // rows of the staging buffer (min(b, n_i) or 0)
+  int64_t stage_class_rows = 0; // rows of the first column class in the buffer
+  size_t off_stage_perm = 0;    // int32 n_stage : buffer row -> X row
+  int32_t classes = 0;          // column classes used for the chunk queues (0 = none)
   // rows handled one per lane group: CSR over list order
   int64_t n_rows = 0, nnz_rows = 0;
   size_t off_rows_ptr = 0;   // uint32 n_rows + 1 (offsets into the level's entry array)
   size_t off_rows_y = 0;     // int32  n_rows      (Y row = perm[p])
-  // chunks handled one per wavefront
-  int64_t n_chunks = 0, nnz_chunks = 0;
+  // chunks handled one per wavefront (the list may contain empty padding slots)
+  int64_t n_chunks = 0, n_real_chunks = 0, nnz_chunks = 0;
   size_t off_chunk_ptr = 0;  // uint32 n_chunks + 1
+  size_t off_chunk_mid = 0;  // uint32 n_chunks : entries before it read the staged head buffer, the rest read X
   size_t off_chunk_dst = 0;  // int32  n_chunks : >= 0 -> Y row (whole row in one chunk), < 0 -> partial slot (-1 - slot)
   // rows assembled from several chunks
   int64_t n_split = 0, n_partials = 0;
@@ -61,31 +71,42 @@ struct LevelImage {
   // entries: first nnz_rows for the row list, then nnz_chunks for the chunk list
   size_t off_entries = 0;
   int64_t x_rows_rows = 0, x_rows_chunks = 0;  // distinct X rows each list references
-  // diagonal blocks whose X window is staged in LDS (optional, may be empty)
+  // diagonal-block tiles processed with their window of P_i X staged in LDS; their entries
+  // follow the chunk entries in the level's entry array
   int64_t n_wtiles = 0, n_wrows = 0, nnz_w = 0;
-  size_t off_wtile = 0;      // WindowTile n_wtiles
+  size_t off_wtiles = 0;     // WindowTile n_wtiles
   size_t off_wrow_ptr = 0;   // uint32 n_wrows + 1
+  size_t off_wrow_mid = 0;   // uint32 n_wrows : entries before it read X rows, the rest index the LDS window
   size_t off_wrow_y = 0;     // int32  n_wrows
-  size_t off_wentries = 0;   // Entry nnz_w, xrow = column position local to the window
 };
 
-// One diagonal block (or a slice of its rows) processed by one workgroup with
-// the block's window of P_i X resident in LDS.
+// Rows [row_begin, row_end) of the window-row list belong to one diagonal block and touch only
+// column positions [win_begin, win_begin + win_count) of it.
 struct WindowTile {
-  uint32_t row_begin, row_end;   // range in the window-row list
-  uint32_t win_begin, win_count; // positions [win_begin, win_begin + win_count) of the level form the window
+  uint32_t row_begin, row_end;
+  uint32_t win_begin, win_count;
 };
 
 struct PackOptions {
   int32_t short_max = 16;     // rows with at most this many entries go to the lane-group list
-  int32_t chunk_nnz = 512;    // nonzeros per wavefront chunk
-  int32_t window_max_rows = 0;// diagonal blocks up to this many rows may use the LDS-window path (0 = off)
+  int32_t chunk_nnz = 256;    // most nonzeros per wavefront chunk
+  int32_t chunk_min = 64;     // windows of a row are merged until a chunk holds this many
+  int32_t window_rows = 4096; // column positions per window of the chunk ordering (0 = row-major chunks)
+  int32_t classes = 0;        // column classes (rounded up to a multiple of 8; 0 = no die queues)
+  int32_t class_gran = 512;   // column positions dealt to a class at a time
+  int32_t class_min = 32;     // a row is split by class when it holds classes * class_min entries
+  int32_t stage_head = 1;     // gather the head rows of level 0 into a contiguous buffer
+  int32_t window_span = 2048; // widest column span of an LDS-window tile (0 = no such tiles)
+  int32_t window_tile_rows = 1024;  // most rows per tile
+  double window_reuse = 2.0;  // a tile is kept when its diagonal-block entries >= this x span
 };
 
 struct Image {
   std::vector<LevelImage> levels;
   std::vector<unsigned char> bytes;  // packed host copy
   int64_t max_partials = 0;
+  int64_t max_stage_rows = 0;
+  int64_t max_window_span = 0;
 };
 
 int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const PackOptions& opt,
@@ -97,23 +118,25 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
 // ---------------------------------------------------------------------------
 struct LaunchTuning {
   int32_t kc = 0;          // column slice width per pass (0 = automatic)
-  int32_t xcd_remap = 1;   // map consecutive work items to the same XCD
-  int32_t unroll = 4;
+  int64_t l2_resident_bytes = 2 << 20;  // share of a die's 4 MiB L2 a resident slice of X_0 may take
 };
 
+// x_rows = rows of X (it decides whether 32-bit offsets are enough).
 int launch_rows(const uint32_t* rows_ptr, const int32_t* rows_y, const Entry* entries,
-                int64_t n_rows, const float* X, float* Y, int32_t k, bool accumulate,
-                const LaunchTuning& t, void* stream);
-int launch_chunks(const uint32_t* chunk_ptr, const int32_t* chunk_dst, const Entry* entries,
-                  int64_t n_chunks, const float* X, float* Y, float* partials, int32_t k,
-                  bool accumulate, const LaunchTuning& t, void* stream);
+                int64_t n_rows, const float* X, int64_t x_rows, float* Y, int32_t k,
+                bool accumulate, const LaunchTuning& t, void* stream);
+int launch_chunks(const uint32_t* chunk_ptr, const uint32_t* chunk_mid, const int32_t* chunk_dst,
+                  const Entry* entries, int64_t n_chunks, const float* X, int64_t x_rows,
+                  const float* Xh, float* Y, float* partials, int32_t k, bool accumulate,
+                  const LaunchTuning& t, void* stream);
 int launch_reduce(const uint32_t* split_ptr, const int32_t* split_y, int64_t n_split,
                   const float* partials, float* Y, int32_t k, bool accumulate, void* stream);
-int launch_window(const WindowTile* tiles, int64_t n_tiles, const uint32_t* wrow_ptr,
-                  const int32_t* wrow_y, const Entry* wentries, const int32_t* perm,
-                  const float* X, float* Y, int32_t k, bool accumulate, void* stream);
 int launch_gather(const int32_t* perm, int64_t n_i, const float* X, float* Xp, int32_t k,
                   void* stream);
-size_t window_lds_bytes_max();
+// max_span = widest window of the tiles (sizes the LDS allocation and the column slice)
+int launch_window(const WindowTile* tiles, int64_t n_tiles, int64_t max_span, const uint32_t* wrow_ptr,
+                  const uint32_t* wrow_mid, const int32_t* wrow_y, const Entry* entries,
+                  const int32_t* perm, const float* X, float* Y, int32_t k, bool accumulate,
+                  void* stream);
 
 }  // namespace arrow

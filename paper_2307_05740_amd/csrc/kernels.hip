@@ -7,31 +7,38 @@
 // which is the axpy leaf of the paper's loop nests (figure "Loop nest for an
 // order 4 TTMc kernel") at order 2, with rows then nonzeros as outer loops
 // (section "SpTTN-Cyclops Framework": sparse indices in stored order).  The
-// row gather P_i X is fused into the loads: entries carry perm[q] directly.
-// The scatter P_i^T is fused into the epilogue: results go to row perm[p] of Y.
+// row gather P_i X is fused into the loads: entries carry perm[q] directly
+// (or the row of the staged head buffer).  The scatter P_i^T is fused into the
+// epilogue: results go to row perm[p] of Y.
 //
 // A lane owns VEC consecutive columns; LPR lanes ("a lane group") cover one
 // slice of LPR*VEC columns; a wavefront holds G = 64 / LPR lane groups.
 //   rows kernel   - one lane group per row (short rows: first-block-column and
 //                   diagonal-block entries of the body rows, short head rows)
-//   chunks kernel - one wavefront per chunk of <= chunk_nnz entries of a long
-//                   row (the head rows); the G lane groups take entries
-//                   round-robin and are combined with wavefront shuffles
+//   chunks kernel - one wavefront per chunk of a long row (the head rows); the
+//                   G lane groups take entries round-robin and are combined
+//                   with wavefront shuffles
 //   reduce kernel - sums the partial vectors of rows that were split into
 //                   several chunks, in a fixed order, and scatters to Y
-//   gather kernel - P_i X materialised (not used by the fused path)
+//   window kernel - diagonal-block tiles with their window of P_i X staged in LDS
+//   gather kernel - rows of P_i X materialised (the staged head X_0, or a whole level)
+// Both product kernels fetch their entries with one coalesced load per batch,
+// park them in a wavefront-private LDS strip and read them back per lane
+// group, so that U row loads are in flight before the first FMA; the SIMDs
+// are 16 lanes wide (4 cycles per wavefront instruction), so the inner loops
+// are written to need one address instruction per row load.
 // No floating-point atomics: results are bitwise reproducible run to run.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <type_traits>
 
 #include "arrow_internal.h"
 
 namespace arrow {
 namespace {
 
-constexpr int kBlock = 256;  // threads per workgroup = 4 wavefronts
-constexpr int kXcds = 8;     // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
+constexpr int kBlock = 64 * kChunksPerGroup;  // threads per workgroup = 4 wavefronts
 
 template <int VEC> struct Vec;
 template <> struct Vec<1> { using type = float; };
@@ -72,82 +79,146 @@ __device__ __forceinline__ void vstore(float* p, typename Vec<VEC>::type v) {
   *reinterpret_cast<typename Vec<VEC>::type*>(p) = v;
 }
 
-// Workgroups are dealt to the 8 dies round-robin; this maps the physical
-// workgroup id to a logical one so that each die walks one contiguous eighth
-// of the work list (its L2 then sees one neighbourhood of rows / windows).
-__device__ __forceinline__ int64_t logical_block(int64_t phys, int64_t per_xcd, int remap) {
-  return remap ? (phys % kXcds) * per_xcd + phys / kXcds : phys;
+// Load VEC columns of row `row` of a row-major matrix.  `base` is wavefront-uniform,
+// col_bytes the lane's byte offset inside a row, row_bytes = 4 k.
+// SMALL: the matrix has at most 2^24 rows and 2^32 bytes, so the byte offset is one 24-bit
+// multiply-add and the load can use (uniform base + 32-bit lane offset) addressing.
+template <int VEC, bool SMALL>
+__device__ __forceinline__ typename Vec<VEC>::type load_row(const char* base, int32_t row,
+                                                            uint32_t row_bytes, uint32_t col_bytes) {
+  if (SMALL) {
+    const uint32_t off = __umul24((uint32_t)row, row_bytes) + col_bytes;
+    return *reinterpret_cast<const typename Vec<VEC>::type*>(base + off);
+  } else {
+    const uint64_t off = (uint64_t)(uint32_t)row * row_bytes + col_bytes;
+    return *reinterpret_cast<const typename Vec<VEC>::type*>(base + off);
+  }
 }
 
-template <int VEC, int LPR, int U>
+__device__ __forceinline__ void strip_sync() {
+  // the strip is written and read by lanes of ONE wavefront: LDS executes a wavefront's
+  // instructions in order, so only the compiler has to be kept from reordering
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// ---------------------------------------------------------------------------
+// rows kernel: lane group per row
+// ---------------------------------------------------------------------------
+template <int VEC, int LPR, int U, bool SMALL>
 __global__ __launch_bounds__(kBlock) void rows_kernel(
     const uint32_t* __restrict__ rows_ptr, const int32_t* __restrict__ rows_y,
     const Entry* __restrict__ ent, int64_t n_rows, const float* __restrict__ X,
-    float* __restrict__ Y, int k, int accumulate, int64_t per_xcd, int remap) {
+    float* __restrict__ Y, int k, int accumulate) {
   using V = typename Vec<VEC>::type;
-  constexpr int GPB = kBlock / LPR;  // lane groups (rows) per workgroup
-  const int64_t blk = logical_block(blockIdx.x, per_xcd, remap);
-  const int64_t r = blk * GPB + threadIdx.x / LPR;
-  const int c = (threadIdx.x % LPR) * VEC + blockIdx.y * (LPR * VEC);
-  if (r >= n_rows || c >= k) return;
-  uint32_t j = rows_ptr[r];
+  constexpr int GPB = kBlock / LPR;             // lane groups (rows) per workgroup
+  constexpr int UU = U < LPR ? U : LPR;         // never read past the group's own strip slots
+  __shared__ Entry strip[kBlock];
+  const int tid = threadIdx.x;
+  const int l = tid % LPR;
+  const int64_t r = (int64_t)blockIdx.x * GPB + tid / LPR;
+  if (r >= n_rows) return;
+  const int c = l * VEC + blockIdx.y * (LPR * VEC);
+  const bool col_ok = c < k;
+  const uint32_t row_bytes = 4u * (uint32_t)k;
+  const uint32_t col_bytes = col_ok ? 4u * (uint32_t)c : 0u;
+  const char* base = reinterpret_cast<const char*>(X);
+  const uint32_t lo = rows_ptr[r];
   const uint32_t hi = rows_ptr[r + 1];
-  const float* __restrict__ Xc = X + c;
+  const Entry* grp = strip + (tid - l);         // the group's LPR slots
   V acc = vzero<VEC>();
-  for (; j + U <= hi; j += U) {
-    Entry e[U];
-    V x[U];
+  for (uint32_t b0 = lo; b0 < hi; b0 += LPR) {
+    const uint32_t nb = hi - b0 < (uint32_t)LPR ? hi - b0 : (uint32_t)LPR;
+    if ((uint32_t)l < nb) strip[tid] = ent[b0 + l];
+    strip_sync();
+    for (uint32_t j = 0; j < nb; j += UU) {
+      Entry e[UU];
+      V x[UU];
 #pragma unroll
-    for (int u = 0; u < U; ++u) e[u] = ent[j + u];
+      for (int u = 0; u < UU; ++u) e[u] = grp[(j + u) % LPR];
 #pragma unroll
-    for (int u = 0; u < U; ++u) x[u] = vload<VEC>(Xc + (size_t)e[u].xrow * (size_t)k);
+      for (int u = 0; u < UU; ++u)
+        x[u] = (j + u < nb) ? load_row<VEC, SMALL>(base, e[u].xrow, row_bytes, col_bytes) : vzero<VEC>();
 #pragma unroll
-    for (int u = 0; u < U; ++u) vfma(acc, e[u].val, x[u]);
+      for (int u = 0; u < UU; ++u) vfma(acc, (j + u < nb) ? e[u].val : 0.f, x[u]);
+    }
+    strip_sync();
   }
-  for (; j < hi; ++j) {
-    Entry e = ent[j];
-    vfma(acc, e.val, vload<VEC>(Xc + (size_t)e.xrow * (size_t)k));
+  if (col_ok) {
+    float* y = Y + (size_t)rows_y[r] * (size_t)k + c;
+    if (accumulate) vadd(acc, vload<VEC>(y));
+    vstore<VEC>(y, acc);
   }
-  float* y = Y + (size_t)rows_y[r] * (size_t)k + c;
-  if (accumulate) vadd(acc, vload<VEC>(y));
-  vstore<VEC>(y, acc);
 }
 
-template <int VEC, int LPR, int U>
+// ---------------------------------------------------------------------------
+// chunks kernel: wavefront per chunk.  Entries [lo, mid) of a chunk read rows of the staged
+// head buffer Xh, entries [mid, hi) read rows of X (the chunk's entries are ordered by
+// column position, head columns first), so the base pointer is uniform inside a batch.
+// ---------------------------------------------------------------------------
+template <int VEC, int LPR, int U, bool SMALL>
 __global__ __launch_bounds__(kBlock) void chunks_kernel(
-    const uint32_t* __restrict__ chunk_ptr, const int32_t* __restrict__ chunk_dst,
-    const Entry* __restrict__ ent, int64_t n_chunks, const float* __restrict__ X,
-    float* __restrict__ Y, float* __restrict__ partials, int k, int accumulate, int64_t per_xcd,
-    int remap) {
+    const uint32_t* __restrict__ chunk_ptr, const uint32_t* __restrict__ chunk_mid,
+    const int32_t* __restrict__ chunk_dst, const Entry* __restrict__ ent, int64_t n_chunks,
+    const float* __restrict__ X, const float* __restrict__ Xh, float* __restrict__ Y,
+    float* __restrict__ partials, int k, int accumulate) {
   using V = typename Vec<VEC>::type;
-  constexpr int G = 64 / LPR;         // lane groups per wavefront
-  constexpr int WPB = kBlock / 64;    // wavefronts (chunks) per workgroup
-  const int64_t blk = logical_block(blockIdx.x, per_xcd, remap);
-  const int64_t ch = blk * WPB + threadIdx.x / 64;
+  constexpr int G = 64 / LPR;
+  constexpr int WPB = kBlock / 64;
+  __shared__ Entry strip[WPB][64];
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / 64));
+  const int64_t ch = (int64_t)blockIdx.x * WPB + wave;
   if (ch >= n_chunks) return;          // whole wavefront leaves together
+  const uint32_t lo = chunk_ptr[ch];
+  const uint32_t hi = chunk_ptr[ch + 1];
+  if (lo == hi) return;                // padding slot of the die queues
+  const uint32_t mid = chunk_mid[ch];
   const int lane = threadIdx.x % 64;
   const int g = lane / LPR;
   const int c = (lane % LPR) * VEC + blockIdx.y * (LPR * VEC);
   const bool col_ok = c < k;
-  const uint32_t lo = chunk_ptr[ch];
-  const uint32_t hi = chunk_ptr[ch + 1];
-  const float* __restrict__ Xc = X + (col_ok ? c : 0);
+  const uint32_t row_bytes = 4u * (uint32_t)k;
+  const uint32_t col_bytes = col_ok ? 4u * (uint32_t)c : 0u;   // lanes past the last column read column 0
+  Entry* mine = strip[wave];
+  const Entry* grp = mine + g;
   V acc = vzero<VEC>();
-  uint32_t j = lo + g;
-  // the lane group g takes entries lo+g, lo+g+G, ...
-  for (; j + (U - 1) * G < hi; j += U * G) {
-    Entry e[U];
-    V x[U];
+  for (int seg = 0; seg < 2; ++seg) {
+    const char* base = reinterpret_cast<const char*>(seg == 0 ? Xh : X);
+    const uint32_t s_lo = seg == 0 ? lo : mid;
+    const uint32_t s_hi = seg == 0 ? mid : hi;
+    for (uint32_t b0 = s_lo; b0 < s_hi; b0 += 64) {
+      const uint32_t nb = s_hi - b0 < 64u ? s_hi - b0 : 64u;
+      if ((uint32_t)lane < nb) mine[lane] = ent[b0 + lane];
+      strip_sync();
+      uint32_t s = 0;                  // step: lane group g handles entry s * G + g
+      for (; (s + U) * G <= nb; s += U) {
+        Entry e[U];
+        V x[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) e[u] = ent[j + u * G];
+        for (int u = 0; u < U; ++u) e[u] = grp[(s + u) * G];
 #pragma unroll
-    for (int u = 0; u < U; ++u) x[u] = vload<VEC>(Xc + (size_t)e[u].xrow * (size_t)k);
+        for (int u = 0; u < U; ++u) x[u] = load_row<VEC, SMALL>(base, e[u].xrow, row_bytes, col_bytes);
 #pragma unroll
-    for (int u = 0; u < U; ++u) vfma(acc, e[u].val, x[u]);
-  }
-  for (; j < hi; j += G) {
-    Entry e = ent[j];
-    vfma(acc, e.val, vload<VEC>(Xc + (size_t)e.xrow * (size_t)k));
+        for (int u = 0; u < U; ++u) vfma(acc, e[u].val, x[u]);
+      }
+      if (s * G < nb) {                // last, partly filled round of this batch
+        Entry e[U];
+        V x[U];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          ok[u] = (s + u) * G + g < nb;
+          e[u] = mine[((s + u) * G + g) % 64];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          x[u] = ok[u] ? load_row<VEC, SMALL>(base, e[u].xrow, row_bytes, col_bytes) : vzero<VEC>();
+#pragma unroll
+        for (int u = 0; u < U; ++u) vfma(acc, ok[u] ? e[u].val : 0.f, x[u]);
+      }
+      strip_sync();                    // the strip is rewritten by the next batch
+    }
   }
   // combine the G lane groups: butterfly over lane-id bits LPR, 2 LPR, ..., 32
 #pragma unroll
@@ -160,6 +231,56 @@ __global__ __launch_bounds__(kBlock) void chunks_kernel(
       vstore<VEC>(y, acc);
     } else {
       vstore<VEC>(partials + (size_t)(-1 - dst) * (size_t)k + c, acc);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// window kernel: one workgroup per tile of a diagonal block.  The tile's window of P_i X
+// (win_count consecutive positions of the level, one column slice of width LPR * VEC) is
+// gathered through perm into LDS once -- the permutation gather of these rows happens here --
+// and every diagonal-block entry of the tile's rows then reads its X row from LDS; the rows'
+// first-block-column entries read X_0 rows from memory.  One lane group per row.
+// ---------------------------------------------------------------------------
+template <int VEC, int LPR>
+__global__ __launch_bounds__(kBlock) void window_kernel(
+    const WindowTile* __restrict__ tiles, const uint32_t* __restrict__ wrow_ptr,
+    const uint32_t* __restrict__ wrow_mid, const int32_t* __restrict__ wrow_y,
+    const Entry* __restrict__ ent, const int32_t* __restrict__ perm, const float* __restrict__ X,
+    float* __restrict__ Y, int k, int accumulate) {
+  using V = typename Vec<VEC>::type;
+  constexpr int GPB = kBlock / LPR;
+  constexpr int W = LPR * VEC;                       // columns per slice = LDS row length
+  extern __shared__ float win[];                     // win_count x W floats
+  const WindowTile t = tiles[blockIdx.x];
+  const int l = threadIdx.x % LPR;
+  const int grp = threadIdx.x / LPR;
+  const int c = l * VEC + blockIdx.y * W;
+  const bool col_ok = c < k;
+  // stage: lane group j loads window rows j, j + GPB, ...
+  for (uint32_t i = grp; i < t.win_count; i += GPB) {
+    V v = vzero<VEC>();
+    if (col_ok) v = vload<VEC>(X + (size_t)perm[t.win_begin + i] * (size_t)k + c);
+    vstore<VEC>(win + (size_t)i * W + l * VEC, v);
+  }
+  __syncthreads();
+  for (uint32_t wr = t.row_begin + grp; wr < t.row_end; wr += GPB) {
+    const uint32_t lo = wrow_ptr[wr], mid = wrow_mid[wr], hi = wrow_ptr[wr + 1];
+    V acc = vzero<VEC>();
+    if (col_ok) {
+      for (uint32_t j = lo; j < mid; ++j) {          // first block column: X_0 rows from memory
+        const Entry e = ent[j];
+        vfma(acc, e.val, vload<VEC>(X + (size_t)e.xrow * (size_t)k + c));
+      }
+    }
+    for (uint32_t j = mid; j < hi; ++j) {            // diagonal block: rows of the LDS window
+      const Entry e = ent[j];
+      vfma(acc, e.val, vload<VEC>(win + (size_t)e.xrow * W + l * VEC));
+    }
+    if (col_ok) {
+      float* y = Y + (size_t)wrow_y[wr] * (size_t)k + c;
+      if (accumulate) vadd(acc, vload<VEC>(y));
+      vstore<VEC>(y, acc);
     }
   }
 }
@@ -182,7 +303,15 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(
   const uint32_t lo = split_ptr[row], hi = split_ptr[row + 1];
   const float* __restrict__ Pc = partials + (col_ok ? c : 0);
   V acc = vzero<VEC>();
-  for (uint32_t s = lo + g; s < hi; s += G) vadd(acc, vload<VEC>(Pc + (size_t)s * (size_t)k));
+  uint32_t s = lo + g;
+  for (; s + 3 * G < hi; s += 4 * G) {
+    V p0 = vload<VEC>(Pc + (size_t)s * (size_t)k);
+    V p1 = vload<VEC>(Pc + (size_t)(s + G) * (size_t)k);
+    V p2 = vload<VEC>(Pc + (size_t)(s + 2 * G) * (size_t)k);
+    V p3 = vload<VEC>(Pc + (size_t)(s + 3 * G) * (size_t)k);
+    vadd(acc, p0); vadd(acc, p1); vadd(acc, p2); vadd(acc, p3);
+  }
+  for (; s < hi; s += G) vadd(acc, vload<VEC>(Pc + (size_t)s * (size_t)k));
 #pragma unroll
   for (int m = LPR; m < 64; m <<= 1) vadd(acc, vshfl_xor(acc, m));
   if (g == 0 && col_ok) {
@@ -240,42 +369,57 @@ int dispatch_shape(const Shape& s, F&& f) {
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
+// 32-bit offsets are enough when a matrix of `rows` rows and k columns stays below 2^24 rows
+// and 2^32 bytes (and a row below 2^24 bytes, for the 24-bit multiply)
+inline bool small_matrix(int64_t rows, int32_t k) {
+  return rows <= (1LL << 24) && rows * (int64_t)k * 4 <= (1LL << 32) && (int64_t)k * 4 < (1LL << 24);
+}
+
 }  // namespace
 
 int launch_rows(const uint32_t* rows_ptr, const int32_t* rows_y, const Entry* entries,
-                int64_t n_rows, const float* X, float* Y, int32_t k, bool accumulate,
-                const LaunchTuning& t, void* stream) {
+                int64_t n_rows, const float* X, int64_t x_rows, float* Y, int32_t k,
+                bool accumulate, const LaunchTuning& t, void* stream) {
   if (n_rows <= 0) return 0;
   const Shape s = pick_shape(k, t.kc);
+  const bool small = small_matrix(x_rows, k);
   return dispatch_shape(s, [&](auto V, auto L) -> int {
     constexpr int VEC = decltype(V)::value, LPR = decltype(L)::value;
     const int64_t blocks = ceil_div(n_rows, kBlock / LPR);
-    const int64_t per_xcd = ceil_div(blocks, kXcds);
-    const int64_t grid_x = t.xcd_remap ? per_xcd * kXcds : blocks;
-    if (grid_x > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
-    dim3 grid((unsigned)grid_x, (unsigned)s.slices);
-    hipLaunchKernelGGL((rows_kernel<VEC, LPR, 4>), grid, dim3(kBlock), 0, (hipStream_t)stream,
-                       rows_ptr, rows_y, entries, n_rows, X, Y, (int)k, accumulate ? 1 : 0,
-                       per_xcd, t.xcd_remap);
+    if (blocks > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
+    dim3 grid((unsigned)blocks, (unsigned)s.slices);
+    if (small)
+      hipLaunchKernelGGL((rows_kernel<VEC, LPR, 8, true>), grid, dim3(kBlock), 0, (hipStream_t)stream,
+                         rows_ptr, rows_y, entries, n_rows, X, Y, (int)k, accumulate ? 1 : 0);
+    else
+      hipLaunchKernelGGL((rows_kernel<VEC, LPR, 8, false>), grid, dim3(kBlock), 0, (hipStream_t)stream,
+                         rows_ptr, rows_y, entries, n_rows, X, Y, (int)k, accumulate ? 1 : 0);
     return (int)hipGetLastError();
   });
 }
 
-int launch_chunks(const uint32_t* chunk_ptr, const int32_t* chunk_dst, const Entry* entries,
-                  int64_t n_chunks, const float* X, float* Y, float* partials, int32_t k,
-                  bool accumulate, const LaunchTuning& t, void* stream) {
+int launch_chunks(const uint32_t* chunk_ptr, const uint32_t* chunk_mid, const int32_t* chunk_dst,
+                  const Entry* entries, int64_t n_chunks, const float* X, int64_t x_rows,
+                  const float* Xh, float* Y, float* partials, int32_t k, bool accumulate,
+                  const LaunchTuning& t, void* stream) {
   if (n_chunks <= 0) return 0;
   const Shape s = pick_shape(k, t.kc);
+  const bool small = small_matrix(x_rows, k);    // the staged buffer has at most as many rows as X
   return dispatch_shape(s, [&](auto V, auto L) -> int {
     constexpr int VEC = decltype(V)::value, LPR = decltype(L)::value;
-    const int64_t blocks = ceil_div(n_chunks, kBlock / 64);
-    const int64_t per_xcd = ceil_div(blocks, kXcds);
-    const int64_t grid_x = t.xcd_remap ? per_xcd * kXcds : blocks;
-    if (grid_x > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
-    dim3 grid((unsigned)grid_x, (unsigned)s.slices);
-    hipLaunchKernelGGL((chunks_kernel<VEC, LPR, 4>), grid, dim3(kBlock), 0, (hipStream_t)stream,
-                       chunk_ptr, chunk_dst, entries, n_chunks, X, Y, partials, (int)k,
-                       accumulate ? 1 : 0, per_xcd, t.xcd_remap);
+    // a multiple of 8 workgroups per column slice, so that workgroup w of every slice runs on
+    // die w mod 8 (the die queues of the chunk list rely on it)
+    const int64_t blocks = ceil_div(ceil_div(n_chunks, kBlock / 64), kDies) * kDies;
+    if (blocks > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
+    dim3 grid((unsigned)blocks, (unsigned)s.slices);
+    if (small)
+      hipLaunchKernelGGL((chunks_kernel<VEC, LPR, 8, true>), grid, dim3(kBlock), 0, (hipStream_t)stream,
+                         chunk_ptr, chunk_mid, chunk_dst, entries, n_chunks, X, Xh, Y, partials,
+                         (int)k, accumulate ? 1 : 0);
+    else
+      hipLaunchKernelGGL((chunks_kernel<VEC, LPR, 8, false>), grid, dim3(kBlock), 0, (hipStream_t)stream,
+                         chunk_ptr, chunk_mid, chunk_dst, entries, n_chunks, X, Xh, Y, partials,
+                         (int)k, accumulate ? 1 : 0);
     return (int)hipGetLastError();
   });
 }
@@ -306,6 +450,29 @@ int launch_gather(const int32_t* perm, int64_t n_i, const float* X, float* Xp, i
     dim3 grid((unsigned)blocks, (unsigned)s.slices);
     hipLaunchKernelGGL((gather_kernel<VEC, LPR>), grid, dim3(kBlock), 0, (hipStream_t)stream, perm,
                        n_i, X, Xp, (int)k);
+    return (int)hipGetLastError();
+  });
+}
+
+int launch_window(const WindowTile* tiles, int64_t n_tiles, int64_t max_span, const uint32_t* wrow_ptr,
+                  const uint32_t* wrow_mid, const int32_t* wrow_y, const Entry* entries,
+                  const int32_t* perm, const float* X, float* Y, int32_t k, bool accumulate,
+                  void* stream) {
+  if (n_tiles <= 0) return 0;
+  // widest column slice whose window still fits the 64 KiB of LDS a workgroup may use
+  const int64_t lds_budget = 64 * 1024;
+  int kc = 256;
+  while (kc > 1 && max_span * kc * 4 > lds_budget) kc >>= 1;
+  if (max_span * kc * 4 > lds_budget) return (int)hipErrorInvalidValue;
+  const Shape s = pick_shape(k, kc);
+  if (max_span * (int64_t)(s.lpr * s.vec) * 4 > lds_budget) return (int)hipErrorInvalidValue;
+  return dispatch_shape(s, [&](auto V, auto L) -> int {
+    constexpr int VEC = decltype(V)::value, LPR = decltype(L)::value;
+    if (n_tiles > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
+    dim3 grid((unsigned)n_tiles, (unsigned)s.slices);
+    const size_t lds = (size_t)max_span * LPR * VEC * sizeof(float);
+    hipLaunchKernelGGL((window_kernel<VEC, LPR>), grid, dim3(kBlock), lds, (hipStream_t)stream, tiles,
+                       wrow_ptr, wrow_mid, wrow_y, entries, perm, X, Y, (int)k, accumulate ? 1 : 0);
     return (int)hipGetLastError();
   });
 }

@@ -81,8 +81,8 @@ def test_all_column_counts(torch, k):
     op.close()
 
 
-@pytest.mark.parametrize("opts", [dict(kc=16), dict(kc=32), dict(kc=64), dict(xcd_remap=0),
-                                  dict(kc=32, xcd_remap=0)])
+@pytest.mark.parametrize("opts", [dict(kc=16), dict(kc=32), dict(kc=64), dict(kc=200),
+                                  dict(l2_resident_bytes=1 << 16)])
 def test_launch_options(torch, opts):
     w = synth.make_config(3, shrink=9)              # R-MAT scale 14, k = 128, b = 512
     X = w.make_x()
@@ -114,6 +114,28 @@ def test_pack_options_short_and_chunk(torch, monkeypatch):
         op.close()
 
 
+@pytest.mark.parametrize("env", [
+    dict(ARROW_CLASSES="0", ARROW_STAGE_HEAD="0"),
+    dict(ARROW_CLASSES="0", ARROW_STAGE_HEAD="1"),
+    dict(ARROW_CLASSES="8", ARROW_CLASS_MIN="2", ARROW_CLASS_GRAN="16"),
+    dict(ARROW_CLASSES="16", ARROW_CLASS_MIN="1", ARROW_CLASS_GRAN="1", ARROW_SHORT_MAX="0"),
+    dict(ARROW_CLASSES="24", ARROW_CLASS_MIN="4", ARROW_CLASS_GRAN="64", ARROW_STAGE_HEAD="0"),
+    dict(ARROW_CLASSES="16", ARROW_CLASS_MIN="8", ARROW_CHUNK_NNZ="16", ARROW_WINDOW_ROWS="128"),
+])
+@pytest.mark.parametrize("k", [16, 128, 36])
+def test_die_queues_and_head_staging(torch, monkeypatch, env, k):
+    """Column classes, die queues with padding slots, and the staged head buffer."""
+    for name, v in env.items():
+        monkeypatch.setenv(name, v)
+    w = synth.make_config(0)
+    X = synth.normal_matrix(w.n, k, seed=9 + k)
+    Yref, B = oracle.spmm(*csr_of(w), X)
+    for opts in (dict(), dict(kc=16)):
+        op, _, Y = run_product(torch, csr_of(w), w.b, X, **opts)
+        assert_within(Y, Yref, B)
+        op.close()
+
+
 def test_grid_one_level(torch):
     w = synth.make_config(1, shrink=4)              # 256 x 256 grid, k = 32, b = 4096
     X = w.make_x()
@@ -126,6 +148,53 @@ def test_grid_one_level(torch):
     Y1 = op.spmm(torch.from_numpy(ones).cuda()).cpu().numpy().reshape(256, 256, 4)
     assert np.all(Y1[1:-1, 1:-1] == 0) and np.all(Y1[0, 1:-1] == 1) and Y1[0, 0, 0] == 2
     op.close()
+
+
+@pytest.mark.parametrize("k", [4, 7, 32, 36, 130])
+def test_diagonal_blocks_with_lds_window(torch, k):
+    """Grid operator: the stencil sits in the diagonal blocks, whose X window is staged in LDS."""
+    w = synth.make_config(1, shrink=6)              # 128 x 128 grid
+    X = synth.normal_matrix(w.n, k, seed=40 + k)
+    op, _, Y = run_product(torch, csr_of(w), 2048, X)
+    lv = op.levels()
+    assert lv[0]["window_tiles"] > 0 and lv[0]["nnz_window"] > 0.5 * w.nnz
+    Yref, B = oracle.spmm(*csr_of(w), X)
+    assert_within(Y, Yref, B)
+    op.close()
+
+
+def test_lds_window_on_a_later_level_accumulates(torch, monkeypatch):
+    """Banded operator plus scattered far entries and a few hubs: with the separator rule off the
+    band is cut at block boundaries, so later levels own banded diagonal blocks and must add."""
+    monkeypatch.setenv("ARROW_SEPARATORS", "0")
+    monkeypatch.setenv("ARROW_WINDOW_REUSE_X10", "5")
+    rng = np.random.default_rng(12)
+    n, b, k = 6000, 500, 20
+    rows, cols = [], []
+    for d in (-3, -2, -1, 0, 1, 2, 3):
+        i = np.arange(max(0, -d), min(n, n - d))
+        rows.append(i); cols.append(i + d)
+    far = rng.integers(0, n, (3000, 2))
+    rows += [far[:, 0], far[:, 1]]; cols += [far[:, 1], far[:, 0]]
+    rows = np.concatenate(rows); cols = np.concatenate(cols)
+    key = np.unique(rows.astype(np.int64) * n + cols)
+    rows, cols = key // n, key % n
+    rowptr = np.zeros(n + 1, np.int64)
+    np.add.at(rowptr, rows + 1, 1)
+    rowptr = np.cumsum(rowptr)
+    colidx = cols.astype(np.int32)
+    vals = synth.fill_uniform(rowptr, colidx, seed=13)
+    X = synth.normal_matrix(n, k, seed=14)
+    op, _, Y = run_product(torch, (rowptr, colidx, vals), b, X)
+    lv = op.levels()
+    assert len(lv) >= 2 and sum(l["window_tiles"] for l in lv) > 0
+    Yref, B = oracle.spmm(rowptr, colidx, vals, X)
+    assert_within(Y, Yref, B)
+    monkeypatch.setenv("ARROW_WINDOW_SPAN", "0")                 # same operand without LDS tiles
+    op2, _, Y2 = run_product(torch, (rowptr, colidx, vals), b, X)
+    assert sum(l["window_tiles"] for l in op2.levels()) == 0
+    assert_within(Y2, Yref, B)
+    op.close(); op2.close()
 
 
 def test_hub_row_is_split_and_reduced(torch):
