@@ -35,14 +35,15 @@ def algorithmic_bytes(levels, n, k):
     per = {}
     for i, L in enumerate(levels):
         rmw = 2 if i > 0 else 1
-        per[("rows", i)] = 8 * L["nnz_rows"] + 8 * L["short_rows"] + 4 + row * (L["x_rows_rows"] + rmw * L["short_rows"])
-        whole = L["chunks"] - L["partials"]
-        per[("chunks", i)] = 8 * L["nnz_chunks"] + 12 * L["chunks"] + 4 + row * (L["x_rows_chunks"] + rmw * whole + L["partials"])
+        whole = L["short_rows"] - L["rows_partials"]
+        per[("rows", i)] = 8 * L["nnz_rows"] + 12 * L["short_rows"] + 4 + row * (L["x_rows_rows"] + rmw * whole + L["rows_partials"])
+        whole = L["chunks"] - L["chunks_partials"]
+        per[("chunks", i)] = 8 * L["nnz_chunks"] + 12 * L["chunks"] + 4 + row * (L["x_rows_chunks"] + rmw * whole + L["chunks_partials"])
         per[("reduce", i)] = 8 * L["split_rows"] + 4 + row * (L["partials"] + rmw * L["split_rows"])
         per[("window", i)] = 8 * L["nnz_window"] + 12 * L["window_rows"] + row * (1 + rmw) * L["window_rows"]
         per[("stage", i)] = 0
     # whole product: X is read at least once and Y written once, whatever the kernel split
-    path = sum(8 * L["nnz"] + 8 * (L["short_rows"] + L["chunks"] + L["window_rows"]) for L in levels) + 2 * row * n
+    path = sum(8 * L["nnz"] + 12 * (L["short_rows"] + L["chunks"] + L["window_rows"]) for L in levels) + 2 * row * n
     path += sum(row * 3 * (L["short_rows"] + L["chunks"] - L["partials"] + L["split_rows"] + L["window_rows"])
                 for L in levels[1:])
     return per, path

@@ -77,8 +77,8 @@ typedef struct arrow_level_info_t {
   int64_t nnz_head_row; /* p < b and q >= b  (first block row, off the corner)   */
   int64_t nnz_head_col; /* p >= b and q < b  (first block column)                */
   int64_t nnz_diag;     /* p >= b and q >= b (then p/b == q/b)                   */
-  int64_t short_rows;   /* rows handled one per lane group                       */
-  int64_t chunks;       /* nonzero chunks handled one per wavefront              */
+  int64_t short_rows;   /* items handled one per lane group (short rows, class pieces) */
+  int64_t chunks;       /* items (chunks of long rows) handled one per wavefront */
   int64_t split_rows;   /* rows whose chunks are combined by the reduction pass  */
   int64_t partials;     /* partial vectors those rows produce (one per chunk)    */
   int64_t nnz_rows;     /* entries held by the lane-group row list               */
@@ -88,6 +88,8 @@ typedef struct arrow_level_info_t {
   int64_t window_tiles; /* diagonal-block tiles run with their X window in LDS   */
   int64_t window_rows;  /* rows those tiles cover                                */
   int64_t nnz_window;   /* entries of those rows                                 */
+  int64_t rows_partials;  /* lane-group items that write a partial vector        */
+  int64_t chunks_partials;/* wavefront items that write a partial vector         */
   int32_t blocks;       /* ceil(n_i / b)                                         */
   int32_t separator_rule; /* 1 if block separators were promoted into the head   */
 } arrow_level_info_t;
@@ -176,6 +178,14 @@ int arrow_export_level(const arrow_handle *h, int32_t level, int32_t *perm,
                        int32_t *rows, int32_t *cols, float *vals);
 
 /*
+ * Host-only consistency check of the packed device image against the levels it was built from:
+ * offsets ordered and in range, row ids inside X / the staging buffer / the LDS windows, every
+ * partial slot written once, every row of every level produced exactly once from exactly its
+ * entries.  Returns ARROW_OK or ARROW_EINTERNAL (text in arrow_last_error).  O(nnz), no GPU.
+ */
+int arrow_self_check(const arrow_handle *h);
+
+/*
  * Launch-time tunables, by name:
  *   "kc"        columns per pass of the chunk kernel; a smaller slice shrinks the working set of
  *               X rows per pass and re-reads the entries k/kc times.  0 = automatic: 64 when the
@@ -190,7 +200,8 @@ int arrow_export_level(const arrow_handle *h, int32_t level, int32_t *perm,
  * holds this many entries, default 64), ARROW_CLASSES (column classes of the die queues, a
  * multiple of 8, default 0 = none), ARROW_CLASS_GRAN (column positions dealt to a class at a time,
  * default 512), ARROW_CLASS_MIN (a row is split by class when it holds classes x this many
- * entries, default 32), ARROW_STAGE_HEAD (1: the head rows of level 0 are gathered into a
+ * entries, default 32), ARROW_PIECE_MAX (a class piece of at most this many entries is handled
+ * by a lane group instead of a wavefront, default 48), ARROW_STAGE_HEAD (1: the head rows of level 0 are gathered into a
  * contiguous buffer before the product), ARROW_WINDOW_SPAN (widest column span of a diagonal-block tile whose
  * window of P_i X is staged in LDS, default 2048, at most 4096, 0 = no such tiles),
  * ARROW_WINDOW_TILE_ROWS (most rows per tile, default 1024), ARROW_WINDOW_REUSE_X10 (a tile is

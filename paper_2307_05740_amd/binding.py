@@ -23,7 +23,7 @@ ARROW_OK, ARROW_EINVAL, ARROW_ENOMEM, ARROW_ENOTREADY, ARROW_ETOOSMALL, ARROW_EH
 EXPORTED = [
     "arrow_decompose", "arrow_device_bytes", "arrow_upload", "arrow_workspace_bytes",
     "arrow_set_workspace", "arrow_spmm", "arrow_spmm_iter", "arrow_gather", "arrow_info",
-    "arrow_level_info", "arrow_export_level", "arrow_set_option", "arrow_set_profiling",
+    "arrow_level_info", "arrow_export_level", "arrow_self_check", "arrow_set_option", "arrow_set_profiling",
     "arrow_get_profile", "arrow_get_level_profile", "arrow_last_error", "arrow_destroy",
 ]
 
@@ -44,7 +44,8 @@ class arrow_level_info_t(ctypes.Structure):
     _fields_ = [(name, ctypes.c_int64) for name in
                 ("n_i", "nnz", "nnz_head_head", "nnz_head_row", "nnz_head_col", "nnz_diag",
                  "short_rows", "chunks", "split_rows", "partials", "nnz_rows", "nnz_chunks",
-                 "x_rows_rows", "x_rows_chunks", "window_tiles", "window_rows", "nnz_window")] + \
+                 "x_rows_rows", "x_rows_chunks", "window_tiles", "window_rows", "nnz_window",
+                 "rows_partials", "chunks_partials")] + \
                [("blocks", ctypes.c_int32), ("separator_rule", ctypes.c_int32)]
 
 
@@ -88,6 +89,8 @@ def lib():
     L.arrow_level_info.argtypes = [vp, i32, ctypes.POINTER(arrow_level_info_t)]
     L.arrow_export_level.restype = ctypes.c_int
     L.arrow_export_level.argtypes = [vp, i32, vp, vp, vp, vp]
+    L.arrow_self_check.restype = ctypes.c_int
+    L.arrow_self_check.argtypes = [vp]
     L.arrow_set_option.restype = ctypes.c_int
     L.arrow_set_option.argtypes = [vp, ctypes.c_char_p, i64]
     L.arrow_set_profiling.restype = ctypes.c_int
@@ -176,6 +179,10 @@ def arrow_export_level(h: int, level: int):
     _check(lib().arrow_export_level(h, level, perm.ctypes.data, rows.ctypes.data, cols.ctypes.data,
                                     vals.ctypes.data))
     return perm, rows, cols, vals
+
+
+def arrow_self_check(h: int) -> None:
+    _check(lib().arrow_self_check(h))
 
 
 def arrow_set_option(h: int, name: str, value: int) -> None:

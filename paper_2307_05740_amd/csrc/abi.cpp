@@ -150,8 +150,16 @@ int product(arrow_handle* h, const float* X, float* Y, int32_t k, hipStream_t st
     }
     if (im.n_rows > 0) {
       Scoped sc(h, kRows, (int)li, stream);
-      int rc = arrow::launch_rows(at<uint32_t>(h, im.off_rows_ptr), at<int32_t>(h, im.off_rows_y), ent,
-                                  im.n_rows, X, h->n, Y, k, acc, h->tuning, stream);
+      // class pieces (die queues) follow the chunk kernel's column slicing; the short rows behind
+      // them run in one pass over whole rows
+      const int64_t np = im.piece_slots;
+      int rc = arrow::launch_rows(at<uint32_t>(h, im.off_rows_ptr), at<uint32_t>(h, im.off_rows_mid),
+                                  at<int32_t>(h, im.off_rows_dst), ent, np, X, h->n, Xh, Y, partials, k,
+                                  acc, tune, stream);
+      if (rc) return check_hip(rc, "rows kernel launch (pieces)");
+      rc = arrow::launch_rows(at<uint32_t>(h, im.off_rows_ptr) + np, at<uint32_t>(h, im.off_rows_mid) + np,
+                              at<int32_t>(h, im.off_rows_dst) + np, ent, im.n_rows - np, X, h->n, Xh, Y,
+                              partials, k, acc, h->tuning, stream);
       if (rc) return check_hip(rc, "rows kernel launch");
     }
     if (im.n_wtiles > 0) {
@@ -232,6 +240,7 @@ int arrow_decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, con
   h->pack.classes = (int32_t)env_int("ARROW_CLASSES", h->pack.classes);
   h->pack.class_gran = (int32_t)env_int("ARROW_CLASS_GRAN", h->pack.class_gran);
   h->pack.class_min = (int32_t)env_int("ARROW_CLASS_MIN", h->pack.class_min);
+  h->pack.piece_max = (int32_t)env_int("ARROW_PIECE_MAX", h->pack.piece_max);
   h->pack.stage_head = (int32_t)env_int("ARROW_STAGE_HEAD", h->pack.stage_head);
   h->pack.window_span = (int32_t)env_int("ARROW_WINDOW_SPAN", h->pack.window_span);
   if (h->pack.window_span > 4096) h->pack.window_span = 4096;   // 4096 positions x 4 columns x 4 B = 64 KiB of LDS
@@ -352,7 +361,8 @@ int arrow_level_info(const arrow_handle* h, int32_t level, arrow_level_info_t* o
   out->nnz = L.rowptr[L.n_i];
   out->nnz_head_head = L.nnz_head_head; out->nnz_head_row = L.nnz_head_row;
   out->nnz_head_col = L.nnz_head_col; out->nnz_diag = L.nnz_diag;
-  out->short_rows = im.n_rows; out->chunks = im.n_real_chunks; out->split_rows = im.n_split;
+  out->short_rows = im.n_real_rows; out->chunks = im.n_real_chunks; out->split_rows = im.n_split;
+  out->rows_partials = im.rows_partials; out->chunks_partials = im.chunks_partials;
   out->partials = im.n_partials; out->nnz_rows = im.nnz_rows; out->nnz_chunks = im.nnz_chunks;
   out->x_rows_rows = im.x_rows_rows; out->x_rows_chunks = im.x_rows_chunks;
   out->window_tiles = im.n_wtiles; out->window_rows = im.n_wrows; out->nnz_window = im.nnz_w;
@@ -375,6 +385,14 @@ int arrow_export_level(const arrow_handle* h, int32_t level, int32_t* perm, int3
     for (int64_t p = 0; p < L.n_i; ++p)
       for (int64_t e = L.rowptr[p]; e < L.rowptr[p + 1]; ++e) rows[e] = (int32_t)p;
   }
+  return ARROW_OK;
+}
+
+int arrow_self_check(const arrow_handle* h) {
+  if (!h) return fail(ARROW_EINVAL, "handle is NULL");
+  std::string err;
+  int rc = arrow::verify_image(h->n, h->b, h->levels, h->img, err);
+  if (rc != ARROW_OK) return fail(rc, "%s", err.c_str());
   return ARROW_OK;
 }
 

@@ -43,7 +43,8 @@ struct Entry {
 };
 
 constexpr int kDies = 8;             // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
-constexpr int kChunksPerGroup = 4;   // wavefronts (chunks) per workgroup of the chunk kernel
+constexpr int kChunksPerGroup = 4;   // wave-list items (one per wavefront) per workgroup of the chunk kernel
+constexpr int kItemsPerGroupBlock = 64;  // group-list items per workgroup of the rows kernel, whatever its lane-group width
 
 struct LevelImage {
   int64_t n_i = 0;
@@ -55,12 +56,14 @@ struct LevelImage {
   int64_t stage_class_rows = 0; // rows of the first column class in the buffer
   size_t off_stage_perm = 0;    // int32 n_stage : buffer row -> X row
   int32_t classes = 0;          // column classes used for the chunk queues (0 = none)
-  // rows handled one per lane group: CSR over list order
-  int64_t n_rows = 0, nnz_rows = 0;
+  // group list: items handled one per lane group (class pieces in die queues, then the short rows)
+  int64_t n_rows = 0, n_real_rows = 0, rows_partials = 0, nnz_rows = 0;
+  int64_t piece_slots = 0;   // slots [0, piece_slots) hold the class pieces (die queues), the rest the short rows
   size_t off_rows_ptr = 0;   // uint32 n_rows + 1 (offsets into the level's entry array)
-  size_t off_rows_y = 0;     // int32  n_rows      (Y row = perm[p])
-  // chunks handled one per wavefront (the list may contain empty padding slots)
-  int64_t n_chunks = 0, n_real_chunks = 0, nnz_chunks = 0;
+  size_t off_rows_mid = 0;   // uint32 n_rows : entries before it read the staged head buffer, the rest read X
+  size_t off_rows_dst = 0;   // int32  n_rows : >= 0 -> Y row, < 0 -> partial slot (-1 - slot), INT32_MIN -> padding
+  // wave list: items handled one per wavefront (the list may contain empty padding slots)
+  int64_t n_chunks = 0, n_real_chunks = 0, chunks_partials = 0, nnz_chunks = 0;
   size_t off_chunk_ptr = 0;  // uint32 n_chunks + 1
   size_t off_chunk_mid = 0;  // uint32 n_chunks : entries before it read the staged head buffer, the rest read X
   size_t off_chunk_dst = 0;  // int32  n_chunks : >= 0 -> Y row (whole row in one chunk), < 0 -> partial slot (-1 - slot)
@@ -95,6 +98,7 @@ struct PackOptions {
   int32_t classes = 0;        // column classes (rounded up to a multiple of 8; 0 = no die queues)
   int32_t class_gran = 512;   // column positions dealt to a class at a time
   int32_t class_min = 32;     // a row is split by class when it holds classes * class_min entries
+  int32_t piece_max = 48;     // a class piece with at most this many entries is a group-list item
   int32_t stage_head = 1;     // gather the head rows of level 0 into a contiguous buffer
   int32_t window_span = 2048; // widest column span of an LDS-window tile (0 = no such tiles)
   int32_t window_tile_rows = 1024;  // most rows per tile
@@ -111,6 +115,9 @@ struct Image {
 
 int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const PackOptions& opt,
                Image& img, std::string& err);
+// host-side consistency check of a packed image (used by arrow_self_check)
+int verify_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const Image& img,
+                 std::string& err);
 
 // ---------------------------------------------------------------------------
 // Kernel launchers (kernels.hip).  All pointers are device pointers; `stream`
@@ -122,9 +129,10 @@ struct LaunchTuning {
 };
 
 // x_rows = rows of X (it decides whether 32-bit offsets are enough).
-int launch_rows(const uint32_t* rows_ptr, const int32_t* rows_y, const Entry* entries,
-                int64_t n_rows, const float* X, int64_t x_rows, float* Y, int32_t k,
-                bool accumulate, const LaunchTuning& t, void* stream);
+int launch_rows(const uint32_t* rows_ptr, const uint32_t* rows_mid, const int32_t* rows_dst,
+                const Entry* entries, int64_t n_rows, const float* X, int64_t x_rows,
+                const float* Xh, float* Y, float* partials, int32_t k, bool accumulate,
+                const LaunchTuning& t, void* stream);
 int launch_chunks(const uint32_t* chunk_ptr, const uint32_t* chunk_mid, const int32_t* chunk_dst,
                   const Entry* entries, int64_t n_chunks, const float* X, int64_t x_rows,
                   const float* Xh, float* Y, float* partials, int32_t k, bool accumulate,

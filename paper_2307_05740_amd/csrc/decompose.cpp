@@ -66,6 +66,51 @@ void bfs_order(int64_t n, const Remainder& R, const std::vector<uint8_t>& active
   }
 }
 
+// Arrangement of the vertices outside `skip` (the head) by a traversal that ignores every
+// entry touching a skipped vertex: depth-first preorder (dfs) or breadth-first order.  Sparse
+// remainders are mostly small trees; a preorder keeps each of them contiguous, so most of their
+// entries end up inside one diagonal block.
+void traversal_order(int64_t n, const Remainder& R, const std::vector<uint8_t>& active,
+                     const std::vector<uint8_t>& skip, bool dfs, std::vector<int32_t>& order) {
+  std::vector<uint8_t> seen(n, 0);
+  order.clear();
+  std::vector<std::pair<int32_t, int64_t>> stack;   // vertex, next entry to look at
+  for (int64_t s = 0; s < n; ++s) {
+    if (!active[s] || skip[s] || seen[s]) continue;
+    seen[s] = 1;
+    order.push_back((int32_t)s);
+    if (dfs) {
+      stack.clear();
+      stack.emplace_back((int32_t)s, R.ptr[s]);
+      while (!stack.empty()) {
+        auto& top = stack.back();
+        const int32_t u = top.first;
+        bool pushed = false;
+        while (top.second < R.ptr[u + 1]) {
+          const int32_t w = R.col[top.second++];
+          if (!seen[w] && active[w] && !skip[w]) {
+            seen[w] = 1;
+            order.push_back(w);
+            stack.emplace_back(w, R.ptr[w]);
+            pushed = true;
+            break;
+          }
+        }
+        if (!pushed) stack.pop_back();
+      }
+    } else {
+      size_t head = order.size() - 1;
+      while (head < order.size()) {
+        const int32_t u = order[head++];
+        for (int64_t p = R.ptr[u]; p < R.ptr[u + 1]; ++p) {
+          const int32_t w = R.col[p];
+          if (!seen[w] && active[w] && !skip[w]) { seen[w] = 1; order.push_back(w); }
+        }
+      }
+    }
+  }
+}
+
 }  // namespace
 
 int decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const float* vals,
@@ -178,8 +223,37 @@ int decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const flo
         std::sort(cand.begin(), cand.begin() + b, by_degree);
         std::vector<uint8_t> in_head(n, 0);
         for (int64_t p = 0; p < b; ++p) { L.perm[p] = cand[p]; in_head[cand[p]] = 1; }
+        // the rest: the given arrangement, or a traversal of what is left without the head --
+        // whichever puts more of the rest-to-rest entries into diagonal blocks
+        std::vector<int32_t> best;
+        int64_t best_cap = -1;
+        std::vector<int32_t> trial;
+        std::vector<int32_t> tpos(n, -1);
+        const int n_cand = opt.bfs_tail ? 3 : 1;
+        for (int cnd = 0; cnd < n_cand; ++cnd) {
+          if (cnd == 0) {
+            trial.clear();
+            for (int32_t v : order) if (!in_head[v]) trial.push_back(v);
+          } else {
+            traversal_order(n, R, active, in_head, cnd == 1, trial);
+          }
+          const int64_t nt = (int64_t)trial.size();
+#pragma omp parallel for schedule(static)
+          for (int64_t t = 0; t < nt; ++t) tpos[trial[t]] = (int32_t)(t / b);
+          int64_t cap = 0;
+#pragma omp parallel for schedule(dynamic, 4096) reduction(+ : cap)
+          for (int64_t t = 0; t < nt; ++t) {
+            const int32_t u = trial[t];
+            const int32_t bu = tpos[u];
+            for (int64_t p = R.ptr[u]; p < R.ptr[u + 1]; ++p) {
+              const int32_t w = R.col[p];
+              if (!in_head[w] && tpos[w] == bu) ++cap;
+            }
+          }
+          if (cap > best_cap) { best_cap = cap; best.swap(trial); }
+        }
         int64_t h = b;
-        for (int32_t v : order) if (!in_head[v]) L.perm[h++] = v;
+        for (int32_t v : best) L.perm[h++] = v;
       }
     }
 #pragma omp parallel for schedule(static)

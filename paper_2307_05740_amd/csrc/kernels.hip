@@ -30,6 +30,7 @@
 // No floating-point atomics: results are bitwise reproducible run to run.
 #include <hip/hip_runtime.h>
 
+#include <climits>
 #include <cstdint>
 #include <type_traits>
 
@@ -104,51 +105,69 @@ __device__ __forceinline__ void strip_sync() {
 }
 
 // ---------------------------------------------------------------------------
-// rows kernel: lane group per row
+// rows kernel: lane group per item of the group list.  A workgroup owns kItemsPerGroupBlock
+// consecutive list slots whatever its lane-group width (the die queues of the list rely on it);
+// its lane groups take them round-robin.  Entries [lo, mid) of an item read rows of the staged
+// head buffer Xh, entries [mid, hi) read rows of X.
 // ---------------------------------------------------------------------------
 template <int VEC, int LPR, int U, bool SMALL>
 __global__ __launch_bounds__(kBlock) void rows_kernel(
-    const uint32_t* __restrict__ rows_ptr, const int32_t* __restrict__ rows_y,
-    const Entry* __restrict__ ent, int64_t n_rows, const float* __restrict__ X,
-    float* __restrict__ Y, int k, int accumulate) {
+    const uint32_t* __restrict__ rows_ptr, const uint32_t* __restrict__ rows_mid,
+    const int32_t* __restrict__ rows_dst, const Entry* __restrict__ ent, int64_t n_rows,
+    const float* __restrict__ X, const float* __restrict__ Xh, float* __restrict__ Y,
+    float* __restrict__ partials, int k, int accumulate) {
   using V = typename Vec<VEC>::type;
-  constexpr int GPB = kBlock / LPR;             // lane groups (rows) per workgroup
+  constexpr int GPB = kBlock / LPR;             // lane groups per workgroup
   constexpr int UU = U < LPR ? U : LPR;         // never read past the group's own strip slots
   __shared__ Entry strip[kBlock];
   const int tid = threadIdx.x;
   const int l = tid % LPR;
-  const int64_t r = (int64_t)blockIdx.x * GPB + tid / LPR;
-  if (r >= n_rows) return;
   const int c = l * VEC + blockIdx.y * (LPR * VEC);
   const bool col_ok = c < k;
   const uint32_t row_bytes = 4u * (uint32_t)k;
-  const uint32_t col_bytes = col_ok ? 4u * (uint32_t)c : 0u;
-  const char* base = reinterpret_cast<const char*>(X);
-  const uint32_t lo = rows_ptr[r];
-  const uint32_t hi = rows_ptr[r + 1];
+  const uint32_t col_bytes = col_ok ? 4u * (uint32_t)c : 0u;   // lanes past the last column read column 0
   const Entry* grp = strip + (tid - l);         // the group's LPR slots
-  V acc = vzero<VEC>();
-  for (uint32_t b0 = lo; b0 < hi; b0 += LPR) {
-    const uint32_t nb = hi - b0 < (uint32_t)LPR ? hi - b0 : (uint32_t)LPR;
-    if ((uint32_t)l < nb) strip[tid] = ent[b0 + l];
-    strip_sync();
-    for (uint32_t j = 0; j < nb; j += UU) {
-      Entry e[UU];
-      V x[UU];
+  const int64_t first = (int64_t)blockIdx.x * kItemsPerGroupBlock;
+  for (int it = tid / LPR; it < kItemsPerGroupBlock; it += GPB) {
+    const int64_t r = first + it;
+    if (r >= n_rows) break;
+    const int32_t dst = rows_dst[r];
+    if (dst == INT32_MIN) continue;             // padding slot of the die queues
+    const uint32_t lo = rows_ptr[r];
+    const uint32_t mid = rows_mid[r];
+    const uint32_t hi = rows_ptr[r + 1];
+    V acc = vzero<VEC>();
+    for (int seg = 0; seg < 2; ++seg) {
+      const char* base = reinterpret_cast<const char*>(seg == 0 ? Xh : X);
+      const uint32_t s_lo = seg == 0 ? lo : mid;
+      const uint32_t s_hi = seg == 0 ? mid : hi;
+      for (uint32_t b0 = s_lo; b0 < s_hi; b0 += LPR) {
+        const uint32_t nb = s_hi - b0 < (uint32_t)LPR ? s_hi - b0 : (uint32_t)LPR;
+        if ((uint32_t)l < nb) strip[tid] = ent[b0 + l];
+        strip_sync();
+        for (uint32_t j = 0; j < nb; j += UU) {
+          Entry e[UU];
+          V x[UU];
 #pragma unroll
-      for (int u = 0; u < UU; ++u) e[u] = grp[(j + u) % LPR];
+          for (int u = 0; u < UU; ++u) e[u] = grp[(j + u) % LPR];
 #pragma unroll
-      for (int u = 0; u < UU; ++u)
-        x[u] = (j + u < nb) ? load_row<VEC, SMALL>(base, e[u].xrow, row_bytes, col_bytes) : vzero<VEC>();
+          for (int u = 0; u < UU; ++u)
+            x[u] = (j + u < nb) ? load_row<VEC, SMALL>(base, e[u].xrow, row_bytes, col_bytes) : vzero<VEC>();
 #pragma unroll
-      for (int u = 0; u < UU; ++u) vfma(acc, (j + u < nb) ? e[u].val : 0.f, x[u]);
+          for (int u = 0; u < UU; ++u) vfma(acc, (j + u < nb) ? e[u].val : 0.f, x[u]);
+        }
+        strip_sync();
+      }
     }
-    strip_sync();
-  }
-  if (col_ok) {
-    float* y = Y + (size_t)rows_y[r] * (size_t)k + c;
-    if (accumulate) vadd(acc, vload<VEC>(y));
-    vstore<VEC>(y, acc);
+    if (col_ok) {
+      if (dst >= 0) {
+        float* y = Y + (size_t)dst * (size_t)k + c;
+        if (accumulate) vadd(acc, vload<VEC>(y));
+        vstore<VEC>(y, acc);
+      } else {
+        vstore<VEC>(partials + (size_t)(-1 - dst) * (size_t)k + c, acc);
+      }
+    }
   }
 }
 
@@ -377,23 +396,27 @@ inline bool small_matrix(int64_t rows, int32_t k) {
 
 }  // namespace
 
-int launch_rows(const uint32_t* rows_ptr, const int32_t* rows_y, const Entry* entries,
-                int64_t n_rows, const float* X, int64_t x_rows, float* Y, int32_t k,
-                bool accumulate, const LaunchTuning& t, void* stream) {
+int launch_rows(const uint32_t* rows_ptr, const uint32_t* rows_mid, const int32_t* rows_dst,
+                const Entry* entries, int64_t n_rows, const float* X, int64_t x_rows,
+                const float* Xh, float* Y, float* partials, int32_t k, bool accumulate,
+                const LaunchTuning& t, void* stream) {
   if (n_rows <= 0) return 0;
   const Shape s = pick_shape(k, t.kc);
   const bool small = small_matrix(x_rows, k);
   return dispatch_shape(s, [&](auto V, auto L) -> int {
     constexpr int VEC = decltype(V)::value, LPR = decltype(L)::value;
-    const int64_t blocks = ceil_div(n_rows, kBlock / LPR);
+    // a multiple of 8 workgroups per column slice: workgroup w of every slice runs on die w mod 8
+    const int64_t blocks = ceil_div(ceil_div(n_rows, kItemsPerGroupBlock), kDies) * kDies;
     if (blocks > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
     dim3 grid((unsigned)blocks, (unsigned)s.slices);
     if (small)
       hipLaunchKernelGGL((rows_kernel<VEC, LPR, 8, true>), grid, dim3(kBlock), 0, (hipStream_t)stream,
-                         rows_ptr, rows_y, entries, n_rows, X, Y, (int)k, accumulate ? 1 : 0);
+                         rows_ptr, rows_mid, rows_dst, entries, n_rows, X, Xh, Y, partials, (int)k,
+                         accumulate ? 1 : 0);
     else
       hipLaunchKernelGGL((rows_kernel<VEC, LPR, 8, false>), grid, dim3(kBlock), 0, (hipStream_t)stream,
-                         rows_ptr, rows_y, entries, n_rows, X, Y, (int)k, accumulate ? 1 : 0);
+                         rows_ptr, rows_mid, rows_dst, entries, n_rows, X, Xh, Y, partials, (int)k,
+                         accumulate ? 1 : 0);
     return (int)hipGetLastError();
   });
 }

@@ -1,39 +1,42 @@
 // Packs the arrow matrices of a decomposition into one flat device image.
 //
-// Per level the image holds the permutation and two work lists that together
-// cover every row position once:
-//   row list   - rows with at most short_max entries, in position order (so the
-//                rows of one diagonal block are neighbours and share their window
-//                of X); a level-0 row without entries is listed too, because
-//                level 0 stores every row of Y.
-//   chunk list - longer rows cut into chunks of at most chunk_nnz entries; a
-//                one-chunk row writes Y directly, a split row writes partial
-//                vectors into consecutive slots that the reduction sums in a
-//                fixed order.
+// Per level the image holds the permutation, the optional LDS-window tiles, and two work
+// lists of ITEMS.  An item is a run of entries of one row together with a destination: a row
+// of Y (the item is the whole row) or a partial-vector slot (the row was cut into several
+// items; the reduction sums its slots, which are consecutive, in a fixed order).
+//   group list - items handled one per lane group: rows with at most short_max entries in
+//                position order (so the rows of one diagonal block are neighbours and share
+//                their window of X; a level-0 row without entries is listed too, because
+//                level 0 stores every row of Y), and the short class pieces of split rows.
+//   wave list  - items handled one per wavefront: chunks of at most chunk_nnz entries.
 //
-// How the chunk list is laid out is what decides where the X rows of the head
-// columns (the window X_0 every block shares) are served from:
-//   * Column classes.  Column positions are dealt to `classes` classes in
-//     granules of class_gran positions.  A row with enough entries is split by
-//     class, and all chunks of class c are placed in workgroup slots that the
-//     hardware hands to accelerator die c mod 8 (workgroups go to the 8 dies
-//     round-robin by workgroup id).  One die therefore only ever touches 1/classes
-//     of X_0 during a phase, a slice small enough to stay resident in its own L2,
-//     and every use of an X row outside the head lands on the same die as well.
-//     classes / 8 phases follow each other; inside a (phase, die) queue the chunks
-//     are ordered by the column window they start in.
-//   * Rows too short to split by class keep whole-row chunks cut at column-window
-//     boundaries and ordered by window; they form the last phase.
-//   * Head staging.  The head rows of P_i X are gathered once per product into a
-//     contiguous buffer, class by class, so a die's slice is one contiguous range.
-//     Chunk entries of head columns carry the row of that buffer; they come first in
-//     every chunk (entries are ordered by column position) and chunk_mid marks where
-//     they end.  All other entries carry perm[q]: the permutation gather stays fused.
+// How the long rows are cut and ordered decides where the X rows of the head columns (the
+// window X_0 every block shares) are served from:
+//   * Column classes (optional).  Column positions are dealt to `classes` classes in granules
+//     of class_gran positions.  A row with at least classes * class_min entries is split by
+//     class; a class piece goes to the group list when it has at most piece_max entries, else
+//     it is chunked into the wave list.  Items of class c sit in workgroup slots that the
+//     hardware hands to accelerator die c mod 8 (workgroups go to the 8 dies round-robin by
+//     workgroup id; a workgroup takes kItemsPerGroupBlock group items or kChunksPerGroup
+//     wave items).  One die therefore only touches 1/classes of X_0 during a phase, a slice
+//     small enough to stay resident in its own L2, and every use of an X row outside the head
+//     lands on the same die as well.  classes / 8 phases follow each other; inside a
+//     (phase, die) queue items are ordered by the column window they start in; queues are
+//     padded with empty slots to equal length.
+//   * Rows not split by class keep whole-row chunks cut at column-window boundaries
+//     (windows are merged until a chunk holds chunk_min entries) and ordered by window, so
+//     that the wavefronts in flight read one neighbourhood of X rows; they form the last phase.
+//   * Head staging.  The head rows of P_i X are gathered once per product into a contiguous
+//     buffer, class by class, so a die's slice is one contiguous range.  Entries of head
+//     columns of long rows carry the row of that buffer; they come first in every item
+//     (entries are ordered by column position) and the item's `mid` marks where they end.
+//     All other entries carry perm[q]: the permutation gather stays fused.
 #include "arrow_internal.h"
 
 #include <omp.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdint>
 #include <cstring>
 
@@ -43,29 +46,31 @@ namespace arrow {
 namespace {
 
 constexpr size_t kAlign = 256;
+constexpr uint32_t kPad = 0xffffffffu;
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Rec {
-  int32_t row;     // row position, -1 for a padding slot
+  int32_t row;     // row position
   uint32_t len;
   int32_t dst;
   uint32_t phase;
   uint32_t key;    // column window of the first entry
-  int32_t queue;   // die queue 0..7, or -1 for the window-ordered last phase
-  uint32_t seq;    // emission index (keeps the sort stable and names the rec)
+  int8_t queue;    // die queue 0..7, or -1 for the window-ordered last phase
+  uint8_t list;    // 0 group list, 1 wave list
+  uint32_t seq;    // emission index (names the rec)
 };
 
 struct Plan {
-  std::vector<int32_t> row_pos;       // positions in the row list
-  std::vector<uint32_t> rows_ptr;     // offsets into the level's entries
-  std::vector<Rec> recs;              // chunk recs in emission order (row by row)
-  std::vector<int64_t> row_first;     // per long row: index of its first rec; parallel to long_rows
-  std::vector<int32_t> long_rows;     // positions of the rows in the chunk list
+  std::vector<int32_t> row_pos;       // plain short rows (group list tail), in position order
+  std::vector<Rec> recs;              // items of the long rows in emission order (row by row)
+  std::vector<int64_t> row_first;     // per long row: index of its first rec
+  std::vector<int32_t> long_rows;     // positions of the long rows
   std::vector<uint8_t> row_split;     // 1 if the row is split by class
-  std::vector<uint32_t> slot_of;      // rec seq -> slot in the final chunk list
-  std::vector<uint32_t> chunk_ptr;    // final list
-  std::vector<int32_t> chunk_dst;
+  std::vector<uint32_t> slot_of;      // rec seq -> slot in its list
+  std::vector<uint32_t> list_ptr[2];  // per list: entry offsets, slots + 1
+  std::vector<int32_t> list_dst[2];   // per list: destination per slot
+  int64_t piece_slots = 0;            // group-list slots before the plain short rows
   std::vector<uint32_t> split_ptr;
   std::vector<int32_t> split_y;
   std::vector<int32_t> stage_perm;    // staged head: buffer row -> original X row
@@ -73,6 +78,43 @@ struct Plan {
   std::vector<int32_t> wrow_pos;      // row positions of the window rows, tile by tile
   std::vector<uint32_t> wrow_ptr;     // offsets of their entries (relative to the level's entries)
 };
+
+// order the recs of one list: class phases as padded die queues, then the last phase in
+// window order; returns rec indices, kPad for padding slots
+std::vector<uint32_t> order_list(const std::vector<Rec>& recs, int list, uint32_t class_phases,
+                                 int unit) {
+  std::vector<uint32_t> order;
+  for (size_t i = 0; i < recs.size(); ++i) if (recs[i].list == list) order.push_back((uint32_t)i);
+  std::stable_sort(order.begin(), order.end(), [&](uint32_t x, uint32_t y) {
+    const Rec& a = recs[x];
+    const Rec& c = recs[y];
+    if (a.phase != c.phase) return a.phase < c.phase;
+    if (a.queue != c.queue) return a.queue < c.queue;
+    return a.key < c.key;
+  });
+  std::vector<uint32_t> out;
+  out.reserve(order.size() + 64);
+  size_t at = 0;
+  for (uint32_t ph = 0; ph < class_phases; ++ph) {
+    size_t qbeg[kDies + 1];
+    for (int q = 0; q < kDies; ++q) {
+      qbeg[q] = at;
+      while (at < order.size() && recs[order[at]].phase == ph && recs[order[at]].queue == q) ++at;
+    }
+    qbeg[kDies] = at;
+    size_t rounds = 0;
+    for (int q = 0; q < kDies; ++q)
+      rounds = std::max(rounds, (qbeg[q + 1] - qbeg[q] + unit - 1) / unit);
+    for (size_t rd = 0; rd < rounds; ++rd)
+      for (int q = 0; q < kDies; ++q)
+        for (int j = 0; j < unit; ++j) {
+          const size_t idx = qbeg[q] + rd * unit + j;
+          out.push_back(idx < qbeg[q + 1] ? order[idx] : kPad);
+        }
+  }
+  while (at < order.size()) out.push_back(order[at++]);   // last phase: plain window order
+  return out;
+}
 
 }  // namespace
 
@@ -89,7 +131,9 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
   const int64_t classes = opt.classes <= 0 ? 0 : (opt.classes + kDies - 1) / kDies * kDies;
   const int64_t gran = opt.class_gran < 1 ? 1 : opt.class_gran;
   const int64_t class_min = opt.class_min < 1 ? 1 : opt.class_min;
+  const int64_t piece_max = opt.piece_max < 0 ? 0 : opt.piece_max;
   const int64_t key_window = window > 0 ? window : 4096;
+  const uint32_t class_phases = (uint32_t)(classes / kDies);
 
   std::vector<Plan> plans(levels.size());
   size_t total = 0;
@@ -153,26 +197,22 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
       }
     }
 
-    // ---- row list -------------------------------------------------------------------------
-    P.rows_ptr.push_back(0);
-    int64_t nnz_rows = 0;
+    // ---- short rows / long rows -------------------------------------------------------------
     for (int64_t p = 0; p < L.n_i; ++p) {
       if (taken[p]) continue;
       const int64_t len = L.rowptr[p + 1] - L.rowptr[p];
       if (len > short_max) { P.long_rows.push_back((int32_t)p); continue; }
       if (len == 0 && li > 0) continue;
       P.row_pos.push_back((int32_t)p);
-      nnz_rows += len;
-      P.rows_ptr.push_back((uint32_t)nnz_rows);
     }
 
-    // ---- chunk recs, row by row -------------------------------------------------------------
+    // ---- items of the long rows, row by row ---------------------------------------------------
     const int64_t n_long = (int64_t)P.long_rows.size();
     P.row_split.assign(n_long, 0);
     std::vector<std::vector<Rec>> per_row(n_long);
 #pragma omp parallel
     {
-      std::vector<int64_t> cnt, start_col;
+      std::vector<int64_t> cnt, first_rec, seen, part, next_at;
 #pragma omp for schedule(dynamic, 64)
       for (int64_t r = 0; r < n_long; ++r) {
         const int32_t p = P.long_rows[r];
@@ -180,14 +220,15 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
         const int32_t* cols = L.colpos.data() + L.rowptr[p];
         std::vector<Rec>& out = per_row[r];
         if (classes > 0 && len >= classes * class_min) {
-          // split by column class; chunk starts are found by a second scan
+          // split by column class; where every part starts is found by a second scan
           P.row_split[r] = 1;
           cnt.assign(classes, 0);
           for (int64_t e = 0; e < len; ++e) ++cnt[(cols[e] / gran) % classes];
-          // part sizes per class
-          std::vector<int64_t> first_rec(classes + 1, 0);
-          for (int64_t c = 0; c < classes; ++c)
-            first_rec[c + 1] = first_rec[c] + (cnt[c] + chunk_nnz - 1) / chunk_nnz;
+          first_rec.assign(classes + 1, 0);
+          for (int64_t c = 0; c < classes; ++c) {
+            const int64_t parts = cnt[c] == 0 ? 0 : (cnt[c] <= piece_max ? 1 : (cnt[c] + chunk_nnz - 1) / chunk_nnz);
+            first_rec[c + 1] = first_rec[c] + parts;
+          }
           out.resize(first_rec[classes]);
           for (int64_t c = 0; c < classes; ++c) {
             const int64_t parts = first_rec[c + 1] - first_rec[c];
@@ -196,11 +237,11 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
             for (int64_t j = 0; j < parts; ++j) {
               Rec& rc = out[first_rec[c] + j];
               rc.row = p; rc.len = (uint32_t)(base + (j < extra ? 1 : 0)); rc.dst = 0;
-              rc.phase = (uint32_t)(c / kDies); rc.queue = (int32_t)(c % kDies); rc.key = 0; rc.seq = 0;
+              rc.phase = (uint32_t)(c / kDies); rc.queue = (int8_t)(c % kDies); rc.key = 0; rc.seq = 0;
+              rc.list = cnt[c] <= piece_max ? 0 : 1;
             }
           }
-          // second scan: the column where every part starts
-          std::vector<int64_t> seen(classes, 0), part(classes, 0), next_at(classes, 0);
+          seen.assign(classes, 0); part.assign(classes, 0); next_at.assign(classes, 0);
           for (int64_t e = 0; e < len; ++e) {
             const int64_t c = (cols[e] / gran) % classes;
             if (seen[c] == next_at[c]) {
@@ -211,6 +252,9 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
             }
             ++seen[c];
           }
+          // lane-group pieces run several to a wavefront: order them by length (longest first)
+          // so that the pieces sharing a wavefront finish together
+          for (Rec& rc : out) if (rc.list == 0) rc.key = 0xffffu - (rc.len > 0xffffu ? 0xffffu : rc.len);
         } else {
           int64_t s0 = 0;
           while (s0 < len) {
@@ -232,8 +276,8 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
               const int64_t sz = base + (j < extra ? 1 : 0);
               Rec rc;
               rc.row = p; rc.len = (uint32_t)sz; rc.dst = 0;
-              rc.phase = (uint32_t)(classes / kDies);              // the last phase
-              rc.queue = -1; rc.key = (uint32_t)(cols[at_row] / key_window); rc.seq = 0;
+              rc.phase = class_phases;                             // the last phase
+              rc.queue = -1; rc.list = 1; rc.key = (uint32_t)(cols[at_row] / key_window); rc.seq = 0;
               out.push_back(rc);
               at_row += sz;
             }
@@ -263,62 +307,45 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
     }
     P.row_first[n_long] = (int64_t)P.recs.size();
     if (slots > 0x7fffffffLL) { err = "too many partial slots"; return ARROW_EINVAL; }
-    if (P.recs.size() > 0x7fffff00ULL) { err = "too many chunks"; return ARROW_EINVAL; }
+    if (P.recs.size() > 0x7fffff00ULL) { err = "too many work items"; return ARROW_EINVAL; }
 
-    // ---- final order: phases, die queues, windows ---------------------------------------------
-    const uint32_t n_phases = (uint32_t)(classes / kDies) + 1;
-    std::vector<uint32_t> order(P.recs.size());
-    for (size_t i = 0; i < order.size(); ++i) order[i] = (uint32_t)i;
-    std::stable_sort(order.begin(), order.end(), [&](uint32_t x, uint32_t y) {
-      const Rec& a = P.recs[x];
-      const Rec& c = P.recs[y];
-      if (a.phase != c.phase) return a.phase < c.phase;
-      if (a.queue != c.queue) return a.queue < c.queue;
-      return a.key < c.key;
-    });
-    // `final_list` holds rec indices, or UINT32_MAX for padding slots
-    std::vector<uint32_t> final_list;
-    final_list.reserve(order.size() + 64);
-    size_t at_o = 0;
-    for (uint32_t ph = 0; ph < n_phases; ++ph) {
-      if (ph + 1 == n_phases) {                      // last phase: plain window order, no queues
-        while (at_o < order.size()) final_list.push_back(order[at_o++]);
-        break;
-      }
-      size_t qbeg[kDies + 1];
-      for (int q = 0; q < kDies; ++q) {
-        qbeg[q] = at_o;
-        while (at_o < order.size() && P.recs[order[at_o]].phase == ph && P.recs[order[at_o]].queue == q) ++at_o;
-      }
-      qbeg[kDies] = at_o;
-      size_t rounds = 0;
-      for (int q = 0; q < kDies; ++q) {
-        const size_t len_q = qbeg[q + 1] - qbeg[q];
-        rounds = std::max(rounds, (len_q + kChunksPerGroup - 1) / kChunksPerGroup);
-      }
-      for (size_t rd = 0; rd < rounds; ++rd)
-        for (int q = 0; q < kDies; ++q)
-          for (int j = 0; j < kChunksPerGroup; ++j) {
-            const size_t idx = qbeg[q] + rd * kChunksPerGroup + j;
-            final_list.push_back(idx < qbeg[q + 1] ? order[idx] : 0xffffffffu);
-          }
-    }
+    // ---- final order of both lists; entry offsets --------------------------------------------
     P.slot_of.assign(P.recs.size(), 0);
-    int64_t at = nnz_rows;
-    P.chunk_ptr.reserve(final_list.size() + 1);
-    P.chunk_dst.reserve(final_list.size());
-    for (size_t s = 0; s < final_list.size(); ++s) {
-      P.chunk_ptr.push_back((uint32_t)at);
-      if (final_list[s] == 0xffffffffu) {
-        P.chunk_dst.push_back(INT32_MIN);            // padding slot: no entries, no output
-      } else {
-        const Rec& rc = P.recs[final_list[s]];
-        P.slot_of[rc.seq] = (uint32_t)s;
-        P.chunk_dst.push_back(rc.dst);
-        at += rc.len;
+    int64_t at = 0;
+    int64_t real_items[2] = {0, 0}, part_items[2] = {0, 0}, list_nnz[2] = {0, 0};
+    for (int list = 0; list < 2; ++list) {
+      const std::vector<uint32_t> fin =
+          order_list(P.recs, list, class_phases, list == 0 ? kItemsPerGroupBlock : kChunksPerGroup);
+      std::vector<uint32_t>& ptr = P.list_ptr[list];
+      std::vector<int32_t>& dst = P.list_dst[list];
+      ptr.reserve(fin.size() + (list == 0 ? P.row_pos.size() : 0) + 1);
+      dst.reserve(fin.size() + (list == 0 ? P.row_pos.size() : 0));
+      const int64_t at0 = at;
+      for (size_t s = 0; s < fin.size(); ++s) {
+        ptr.push_back((uint32_t)at);
+        if (fin[s] == kPad) {
+          dst.push_back(INT32_MIN);                  // padding slot: no entries, no output
+        } else {
+          const Rec& rc = P.recs[fin[s]];
+          P.slot_of[rc.seq] = (uint32_t)s;
+          dst.push_back(rc.dst);
+          at += rc.len;
+          ++real_items[list];
+          if (rc.dst < 0) ++part_items[list];
+        }
       }
+      if (list == 0) {
+        P.piece_slots = (int64_t)fin.size();
+        for (int32_t p : P.row_pos) {                // plain short rows follow the class pieces
+          ptr.push_back((uint32_t)at);
+          dst.push_back(L.perm[p]);
+          at += L.rowptr[p + 1] - L.rowptr[p];
+          ++real_items[0];
+        }
+      }
+      ptr.push_back((uint32_t)at);
+      list_nnz[list] = at - at0;
     }
-    P.chunk_ptr.push_back((uint32_t)at);
     if (at + nnz_w != lev_nnz) { err = "work lists do not cover the level"; return ARROW_EINTERNAL; }
     P.wrow_ptr.reserve(P.wrow_pos.size() + 1);
     for (int32_t p : P.wrow_pos) { P.wrow_ptr.push_back((uint32_t)at); at += L.rowptr[p + 1] - L.rowptr[p]; }
@@ -339,22 +366,27 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
       }
     }
 
-    im.n_rows = (int64_t)P.row_pos.size();
-    im.nnz_rows = nnz_rows;
-    im.n_chunks = (int64_t)P.chunk_dst.size();
-    im.n_real_chunks = (int64_t)P.recs.size();
-    im.nnz_chunks = lev_nnz - nnz_rows - nnz_w;
+    im.piece_slots = P.piece_slots;
+    im.n_rows = (int64_t)P.list_dst[0].size();
+    im.n_real_rows = real_items[0];
+    im.rows_partials = part_items[0];
+    im.nnz_rows = list_nnz[0];
+    im.n_chunks = (int64_t)P.list_dst[1].size();
+    im.n_real_chunks = real_items[1];
+    im.chunks_partials = part_items[1];
+    im.nnz_chunks = list_nnz[1];
+    im.n_split = (int64_t)P.split_y.size();
+    im.n_partials = slots;
     im.n_wtiles = (int64_t)P.wtiles.size();
     im.n_wrows = (int64_t)P.wrow_pos.size();
     im.nnz_w = nnz_w;
-    im.n_split = (int64_t)P.split_y.size();
-    im.n_partials = slots;
     if (slots > img.max_partials) img.max_partials = slots;
 
     im.off_perm = total;        total = align_up(total + sizeof(int32_t) * (size_t)L.n_i);
     im.off_stage_perm = total;  total = align_up(total + sizeof(int32_t) * (size_t)im.n_stage);
     im.off_rows_ptr = total;    total = align_up(total + sizeof(uint32_t) * (size_t)(im.n_rows + 1));
-    im.off_rows_y = total;      total = align_up(total + sizeof(int32_t) * (size_t)im.n_rows);
+    im.off_rows_mid = total;    total = align_up(total + sizeof(uint32_t) * (size_t)im.n_rows);
+    im.off_rows_dst = total;    total = align_up(total + sizeof(int32_t) * (size_t)im.n_rows);
     im.off_chunk_ptr = total;   total = align_up(total + sizeof(uint32_t) * (size_t)(im.n_chunks + 1));
     im.off_chunk_mid = total;   total = align_up(total + sizeof(uint32_t) * (size_t)im.n_chunks);
     im.off_chunk_dst = total;   total = align_up(total + sizeof(int32_t) * (size_t)im.n_chunks);
@@ -381,17 +413,20 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
     LevelImage& im = img.levels[li];
     std::memcpy(base + im.off_perm, L.perm.data(), sizeof(int32_t) * (size_t)L.n_i);
     if (im.n_stage) std::memcpy(base + im.off_stage_perm, P.stage_perm.data(), sizeof(int32_t) * (size_t)im.n_stage);
-    std::memcpy(base + im.off_rows_ptr, P.rows_ptr.data(), sizeof(uint32_t) * P.rows_ptr.size());
-    std::memcpy(base + im.off_chunk_ptr, P.chunk_ptr.data(), sizeof(uint32_t) * P.chunk_ptr.size());
-    if (!P.chunk_dst.empty())
-      std::memcpy(base + im.off_chunk_dst, P.chunk_dst.data(), sizeof(int32_t) * P.chunk_dst.size());
+    std::memcpy(base + im.off_rows_ptr, P.list_ptr[0].data(), sizeof(uint32_t) * P.list_ptr[0].size());
+    std::memcpy(base + im.off_chunk_ptr, P.list_ptr[1].data(), sizeof(uint32_t) * P.list_ptr[1].size());
+    if (im.n_rows) std::memcpy(base + im.off_rows_dst, P.list_dst[0].data(), sizeof(int32_t) * (size_t)im.n_rows);
+    if (im.n_chunks) std::memcpy(base + im.off_chunk_dst, P.list_dst[1].data(), sizeof(int32_t) * (size_t)im.n_chunks);
     std::memcpy(base + im.off_split_ptr, P.split_ptr.data(), sizeof(uint32_t) * P.split_ptr.size());
     if (!P.split_y.empty())
       std::memcpy(base + im.off_split_y, P.split_y.data(), sizeof(int32_t) * P.split_y.size());
-    int32_t* rows_y = reinterpret_cast<int32_t*>(base + im.off_rows_y);
-    uint32_t* chunk_mid = reinterpret_cast<uint32_t*>(base + im.off_chunk_mid);
+    uint32_t* list_mid[2] = {reinterpret_cast<uint32_t*>(base + im.off_rows_mid),
+                             reinterpret_cast<uint32_t*>(base + im.off_chunk_mid)};
     Entry* ent = reinterpret_cast<Entry*>(base + im.off_entries);
-    for (int64_t c = 0; c < im.n_chunks; ++c) chunk_mid[c] = P.chunk_ptr[c];   // no staged entries yet
+    for (int list = 0; list < 2; ++list) {           // default: no staged entries in the item
+      const int64_t cnt = list == 0 ? im.n_rows : im.n_chunks;
+      for (int64_t s = 0; s < cnt; ++s) list_mid[list][s] = P.list_ptr[list][s];
+    }
 
     // row of the staging buffer that holds head column position q
     const int64_t ncls = im.classes > 0 ? im.classes : 1;
@@ -407,17 +442,19 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
       return (int32_t)(cbase[c] + rank);
     };
 
-    const int64_t n_rows = im.n_rows;
+    // plain short rows: they always read X itself
+    const int64_t n_plain = (int64_t)P.row_pos.size();
 #pragma omp parallel for schedule(dynamic, 4096)
-    for (int64_t r = 0; r < n_rows; ++r) {
+    for (int64_t r = 0; r < n_plain; ++r) {
       const int32_t p = P.row_pos[r];
-      rows_y[r] = L.perm[p];
       int64_t src = L.rowptr[p];
-      for (uint32_t e = P.rows_ptr[r]; e < P.rows_ptr[r + 1]; ++e, ++src) {
-        ent[e].xrow = L.perm[L.colpos[src]];       // the row list always reads X itself
+      const int64_t slot = P.piece_slots + r;
+      for (uint32_t e = P.list_ptr[0][slot]; e < P.list_ptr[0][slot + 1]; ++e, ++src) {
+        ent[e].xrow = L.perm[L.colpos[src]];
         ent[e].val = L.vals[src];
       }
     }
+    // long rows: items in emission order
     const int64_t n_long = (int64_t)P.long_rows.size();
     const int64_t classes = im.classes;
 #pragma omp parallel
@@ -431,9 +468,8 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
         const int64_t src0 = L.rowptr[p];
         const int32_t* cols = L.colpos.data() + src0;
         const int64_t rec0 = P.row_first[r], rec1 = P.row_first[r + 1];
-        // the row's entries in emission order
         const int64_t* seq = nullptr;
-        if (P.row_split[r]) {
+        if (P.row_split[r]) {                        // the row's entries class by class
           fill.assign(classes + 1, 0);
           for (int64_t e = 0; e < len; ++e) ++fill[(cols[e] / gran) % classes + 1];
           for (int64_t c = 0; c < classes; ++c) fill[c + 1] += fill[c];
@@ -443,14 +479,15 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
         }
         int64_t k_in_row = 0;
         for (int64_t rc = rec0; rc < rec1; ++rc) {
+          const int list = P.recs[rc].list;
           const uint32_t slot = P.slot_of[rc];
-          uint32_t e_out = P.chunk_ptr[slot];
-          const uint32_t e_end = P.chunk_ptr[slot + 1];
+          uint32_t e_out = P.list_ptr[list][slot];
+          const uint32_t e_end = P.list_ptr[list][slot + 1];
           uint32_t staged_here = 0;
           for (; e_out < e_end; ++e_out, ++k_in_row) {
             const int64_t e = seq ? seq[k_in_row] : k_in_row;
             const int32_t q = cols[e];
-            if (im.staged && q < im.n_stage) {     // head column: comes before every other column
+            if (im.staged && q < im.n_stage) {       // head column: comes before every other column
               ent[e_out].xrow = stage_row(q);
               ++staged_here;
             } else {
@@ -458,7 +495,7 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
             }
             ent[e_out].val = L.vals[src0 + e];
           }
-          chunk_mid[slot] = P.chunk_ptr[slot] + staged_here;
+          list_mid[list][slot] = P.list_ptr[list][slot] + staged_here;
         }
       }
     }
@@ -491,25 +528,137 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
     }
     // distinct X rows per list (what each kernel must read at least once)
     std::vector<uint8_t> seen((size_t)n, 0);
-    for (int pass = 0; pass < 2; ++pass) {
-      const int64_t lo = pass == 0 ? 0 : im.nnz_rows;
-      const int64_t hi = pass == 0 ? im.nnz_rows : im.nnz_rows + im.nnz_chunks;
+    for (int list = 0; list < 2; ++list) {
       std::fill(seen.begin(), seen.end(), 0);
-      if (pass == 0) {
-#pragma omp parallel for schedule(static)
-        for (int64_t e = lo; e < hi; ++e) seen[ent[e].xrow] = 1;
-      } else {
-#pragma omp parallel for schedule(dynamic, 1024)
-        for (int64_t c = 0; c < im.n_chunks; ++c) {
-          for (uint32_t e = P.chunk_ptr[c]; e < chunk_mid[c]; ++e) seen[P.stage_perm[ent[e].xrow]] = 1;
-          for (uint32_t e = chunk_mid[c]; e < P.chunk_ptr[c + 1]; ++e) seen[ent[e].xrow] = 1;
-        }
+      const int64_t cnt_items = list == 0 ? im.n_rows : im.n_chunks;
+      const std::vector<uint32_t>& ptr = P.list_ptr[list];
+      const uint32_t* mid = list_mid[list];
+#pragma omp parallel for schedule(dynamic, 4096)
+      for (int64_t s = 0; s < cnt_items; ++s) {
+        for (uint32_t e = ptr[s]; e < mid[s]; ++e) seen[P.stage_perm[ent[e].xrow]] = 1;
+        for (uint32_t e = mid[s]; e < ptr[s + 1]; ++e) seen[ent[e].xrow] = 1;
       }
       int64_t cnt = 0;
 #pragma omp parallel for schedule(static) reduction(+ : cnt)
       for (int64_t v = 0; v < n; ++v) cnt += seen[v];
-      (pass == 0 ? im.x_rows_rows : im.x_rows_chunks) = cnt;
+      (list == 0 ? im.x_rows_rows : im.x_rows_chunks) = cnt;
     }
+  }
+  return ARROW_OK;
+}
+
+// Consistency of a packed image against the levels it was built from: offsets in range and
+// ordered, row ids inside X / the staging buffer / the LDS window, every partial slot written
+// by exactly one item and owned by exactly one split row, and every row of a level produced
+// exactly once (level 0: every vertex).
+int verify_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const Image& img,
+                 std::string& err) {
+  if (img.levels.size() != levels.size()) { err = "level count differs"; return ARROW_EINTERNAL; }
+  const unsigned char* base = img.bytes.data();
+  for (size_t li = 0; li < levels.size(); ++li) {
+    const HostLevel& L = levels[li];
+    const LevelImage& im = img.levels[li];
+    const int64_t lev_nnz = L.rowptr[L.n_i];
+    const Entry* ent = reinterpret_cast<const Entry*>(base + im.off_entries);
+    const int32_t* stage_perm = reinterpret_cast<const int32_t*>(base + im.off_stage_perm);
+    std::vector<int32_t> produced(n, 0);      // times a Y row is written (directly or by the reduction)
+    std::vector<int32_t> slot_writes(im.n_partials, 0);
+    std::vector<double> checksum(n, 0.0);     // sum over the row's entries of value * (1 + X row id)
+    std::vector<double> slot_sum(im.n_partials, 0.0);
+    int64_t covered = 0;
+    const uint32_t* ptrs[2] = {reinterpret_cast<const uint32_t*>(base + im.off_rows_ptr),
+                               reinterpret_cast<const uint32_t*>(base + im.off_chunk_ptr)};
+    const uint32_t* mids[2] = {reinterpret_cast<const uint32_t*>(base + im.off_rows_mid),
+                               reinterpret_cast<const uint32_t*>(base + im.off_chunk_mid)};
+    const int32_t* dsts[2] = {reinterpret_cast<const int32_t*>(base + im.off_rows_dst),
+                              reinterpret_cast<const int32_t*>(base + im.off_chunk_dst)};
+    const int64_t cnts[2] = {im.n_rows, im.n_chunks};
+    uint32_t expect = 0;
+    for (int list = 0; list < 2; ++list) {
+      for (int64_t s = 0; s < cnts[list]; ++s) {
+        const uint32_t lo = ptrs[list][s], mid = mids[list][s], hi = ptrs[list][s + 1];
+        if (lo != expect || lo > mid || mid > hi || (int64_t)hi > lev_nnz) { err = "item offsets out of order"; return ARROW_EINTERNAL; }
+        expect = hi;
+        const int32_t dst = dsts[list][s];
+        if (dst == INT32_MIN) { if (hi != lo) { err = "padding slot with entries"; return ARROW_EINTERNAL; } continue; }
+        double sum = 0.0;
+        for (uint32_t e = lo; e < hi; ++e) {
+          int64_t xr = ent[e].xrow;
+          if (e < mid) { if (xr < 0 || xr >= im.n_stage) { err = "staged row out of range"; return ARROW_EINTERNAL; } xr = stage_perm[xr]; }
+          if (xr < 0 || xr >= n) { err = "X row out of range"; return ARROW_EINTERNAL; }
+          sum += (double)ent[e].val * (double)(1 + xr);
+        }
+        covered += hi - lo;
+        if (dst >= 0) {
+          if (dst >= n) { err = "Y row out of range"; return ARROW_EINTERNAL; }
+          ++produced[dst]; checksum[dst] += sum;
+        } else {
+          const int64_t slot = -1 - (int64_t)dst;
+          if (slot >= im.n_partials) { err = "partial slot out of range"; return ARROW_EINTERNAL; }
+          ++slot_writes[slot]; slot_sum[slot] += sum;
+        }
+      }
+    }
+    // split rows own consecutive slots
+    const uint32_t* sp = reinterpret_cast<const uint32_t*>(base + im.off_split_ptr);
+    const int32_t* sy = reinterpret_cast<const int32_t*>(base + im.off_split_y);
+    if (sp[0] != 0 || (int64_t)sp[im.n_split] != im.n_partials) { err = "split table does not cover the slots"; return ARROW_EINTERNAL; }
+    for (int64_t r = 0; r < im.n_split; ++r) {
+      if (sp[r] >= sp[r + 1] || sy[r] < 0 || sy[r] >= n) { err = "bad split row"; return ARROW_EINTERNAL; }
+      ++produced[sy[r]];
+      for (uint32_t sl = sp[r]; sl < sp[r + 1]; ++sl) checksum[sy[r]] += slot_sum[sl];
+    }
+    for (int64_t sl = 0; sl < im.n_partials; ++sl)
+      if (slot_writes[sl] != 1) { err = "a partial slot is not written exactly once"; return ARROW_EINTERNAL; }
+    // window tiles
+    const WindowTile* wt = reinterpret_cast<const WindowTile*>(base + im.off_wtiles);
+    const uint32_t* wp = reinterpret_cast<const uint32_t*>(base + im.off_wrow_ptr);
+    const uint32_t* wm = reinterpret_cast<const uint32_t*>(base + im.off_wrow_mid);
+    const int32_t* wy = reinterpret_cast<const int32_t*>(base + im.off_wrow_y);
+    uint32_t wexpect = 0;
+    for (int64_t t = 0; t < im.n_wtiles; ++t) {
+      if (wt[t].row_begin != wexpect || wt[t].row_end <= wt[t].row_begin || (int64_t)wt[t].row_end > im.n_wrows ||
+          (int64_t)wt[t].win_begin + wt[t].win_count > L.n_i || (int64_t)wt[t].win_count > img.max_window_span) {
+        err = "bad window tile"; return ARROW_EINTERNAL;
+      }
+      wexpect = wt[t].row_end;
+      for (uint32_t wr = wt[t].row_begin; wr < wt[t].row_end; ++wr) {
+        const uint32_t lo = wp[wr], mid = wm[wr], hi = wp[wr + 1];
+        if (lo != expect || lo > mid || mid > hi || (int64_t)hi > lev_nnz) { err = "window row offsets out of order"; return ARROW_EINTERNAL; }
+        expect = hi;
+        if (wy[wr] < 0 || wy[wr] >= n) { err = "window Y row out of range"; return ARROW_EINTERNAL; }
+        ++produced[wy[wr]];
+        double sum = 0.0;
+        for (uint32_t e = lo; e < hi; ++e) {
+          int64_t xr = ent[e].xrow;
+          if (e >= mid) {
+            if (xr < 0 || xr >= wt[t].win_count) { err = "window column out of range"; return ARROW_EINTERNAL; }
+            xr = L.perm[wt[t].win_begin + xr];
+          }
+          if (xr < 0 || xr >= n) { err = "X row out of range"; return ARROW_EINTERNAL; }
+          sum += (double)ent[e].val * (double)(1 + xr);
+        }
+        checksum[wy[wr]] += sum;
+        covered += hi - lo;
+      }
+    }
+    if (wexpect != (uint32_t)im.n_wrows) { err = "window rows not covered by tiles"; return ARROW_EINTERNAL; }
+    if (covered != lev_nnz) { err = "entries not covered exactly once"; return ARROW_EINTERNAL; }
+    // every row of the level produced exactly once, with the right entries
+    for (int64_t p = 0; p < L.n_i; ++p) {
+      const int32_t v = L.perm[p];
+      const int64_t len = L.rowptr[p + 1] - L.rowptr[p];
+      const int want = (li == 0 || len > 0) ? 1 : 0;
+      if (produced[v] != want) { err = "a row of Y is not produced exactly once"; return ARROW_EINTERNAL; }
+      double sum = 0.0;
+      for (int64_t e = L.rowptr[p]; e < L.rowptr[p + 1]; ++e)
+        sum += (double)L.vals[e] * (double)(1 + L.perm[L.colpos[e]]);
+      const double tol = 1e-9 * (1.0 + std::abs(sum)) * (double)(len + 1);
+      if (std::abs(sum - checksum[v]) > tol) { err = "a row's entries differ between level and image"; return ARROW_EINTERNAL; }
+      produced[v] = 0;
+    }
+    for (int64_t v = 0; v < n; ++v) if (produced[v] != 0) { err = "a vertex outside the level is written"; return ARROW_EINTERNAL; }
+    (void)b;
   }
   return ARROW_OK;
 }

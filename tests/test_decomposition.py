@@ -20,6 +20,7 @@ def _lib_built():
 def decompose_and_export(rowptr, colidx, vals, b):
     h = binding.arrow_decompose(rowptr, colidx, vals, b)
     try:
+        binding.arrow_self_check(h)                      # the packed device image matches the levels
         info = binding.arrow_info(h)
         levels = [binding.arrow_export_level(h, i) for i in range(info["levels"])]
         linfo = [binding.arrow_level_info(h, i) for i in range(info["levels"])]
@@ -139,6 +140,9 @@ def test_single_crossing_entry_needs_two_levels_with_plain_rule(monkeypatch):
         rows += [u, v]; cols += [v, u]
     rp, ci, va = csr_from_coo(n, np.array(rows), np.array(cols), np.arange(1, len(rows) + 1, dtype=np.float64))
     info, _, _ = full_check(rp, ci, va, 2, np.eye(n, dtype=np.float32)[:, :5].copy())
+    assert info["levels"] == 1    # the traversal arrangement puts the partners next to each other
+    monkeypatch.setenv("ARROW_BFS_TAIL", "0")            # id order keeps them in different blocks
+    info, _, _ = full_check(rp, ci, va, 2, np.eye(n, dtype=np.float32)[:, :5].copy())
     assert info["levels"] == 2
 
 
@@ -198,6 +202,26 @@ def test_error_paths():
     finally:
         binding.arrow_destroy(h)
     binding.arrow_destroy(None)                          # NULL is ignored
+
+
+@pytest.mark.parametrize("env", [
+    dict(ARROW_CLASSES="16", ARROW_CLASS_MIN="2", ARROW_CLASS_GRAN="16"),
+    dict(ARROW_CLASSES="8", ARROW_CLASS_MIN="1", ARROW_PIECE_MAX="0", ARROW_SHORT_MAX="0"),
+    dict(ARROW_CLASSES="24", ARROW_CLASS_MIN="3", ARROW_PIECE_MAX="1000", ARROW_STAGE_HEAD="0"),
+    dict(ARROW_WINDOW_ROWS="0", ARROW_CHUNK_NNZ="7", ARROW_SHORT_MAX="3"),
+    dict(ARROW_WINDOW_ROWS="64", ARROW_CHUNK_MIN="5", ARROW_CHUNK_NNZ="40"),
+    dict(ARROW_WINDOW_SPAN="0"), dict(ARROW_WINDOW_SPAN="4096", ARROW_WINDOW_REUSE_X10="1"),
+])
+def test_packed_image_self_check_under_pack_options(monkeypatch, env):
+    for name, v in env.items():
+        monkeypatch.setenv(name, v)
+    for idx, shrink, b in ((0, 0, 512), (1, 8, 1024), (2, 8, None), (4, 10, None)):
+        w = synth.make_config(idx, shrink=shrink)
+        h = binding.arrow_decompose(w.rowptr, w.colidx, w.vals, b or w.b)
+        try:
+            binding.arrow_self_check(h)
+        finally:
+            binding.arrow_destroy(h)
 
 
 def test_library_exports_every_declared_symbol():

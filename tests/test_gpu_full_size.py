@@ -80,3 +80,24 @@ def test_config3_rmat_s23_k128_sampled_rows(torch):
     scale = np.abs(ata) @ np.abs(X.astype(np.float64))
     assert np.all(np.abs(colsum.cpu().numpy() - want) <= 1e-5 * scale)
     op.close()
+
+
+def test_config4_chung_lu_16m_fifth_power_sampled(torch):
+    """Chung-Lu, n = 16,777,216, row-normalised, A^5.X with k = 32: hub-heavy arrow heads and
+    many levels.  The fp64 iterate is computed in full by the oracle (17 GB of host memory)."""
+    print("generating Chung-Lu n=2^24 ...", flush=True)
+    w = synth.make_config(4)
+    print(f"decomposing n={w.n} nnz={w.nnz} ...", flush=True)
+    op = binding.ArrowSpMM(w.rowptr, w.colidx, w.vals, w.b)
+    X = w.make_x()
+    Xd = torch.from_numpy(X).cuda()
+    print(f"levels={op.info['levels']}; five chained products ...", flush=True)
+    op.spmm_iter(Xd, w.l)
+    torch.cuda.synchronize()
+    print("oracle: five fp64 products ...", flush=True)
+    Xl, El = oracle.spmm_iter(w.rowptr, w.colidx, w.vals, X, w.l)
+    got = Xd.cpu().numpy()
+    # whole result, in slabs to bound temporaries
+    for s in range(0, w.n, 1 << 21):
+        check(got[s:s + (1 << 21)], Xl[s:s + (1 << 21)], El[s:s + (1 << 21)], scale=w.l)
+    op.close()

@@ -121,6 +121,9 @@ def test_pack_options_short_and_chunk(torch, monkeypatch):
     dict(ARROW_CLASSES="16", ARROW_CLASS_MIN="1", ARROW_CLASS_GRAN="1", ARROW_SHORT_MAX="0"),
     dict(ARROW_CLASSES="24", ARROW_CLASS_MIN="4", ARROW_CLASS_GRAN="64", ARROW_STAGE_HEAD="0"),
     dict(ARROW_CLASSES="16", ARROW_CLASS_MIN="8", ARROW_CHUNK_NNZ="16", ARROW_WINDOW_ROWS="128"),
+    dict(ARROW_CLASSES="16", ARROW_CLASS_MIN="2", ARROW_PIECE_MAX="0"),
+    dict(ARROW_CLASSES="16", ARROW_CLASS_MIN="2", ARROW_PIECE_MAX="1000000", ARROW_CLASS_GRAN="32"),
+    dict(ARROW_CLASSES="8", ARROW_CLASS_MIN="3", ARROW_PIECE_MAX="5", ARROW_SHORT_MAX="2"),
 ])
 @pytest.mark.parametrize("k", [16, 128, 36])
 def test_die_queues_and_head_staging(torch, monkeypatch, env, k):
