@@ -245,6 +245,7 @@ int arrow_decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, con
   h->pack.window_span = (int32_t)env_int("ARROW_WINDOW_SPAN", h->pack.window_span);
   if (h->pack.window_span > 4096) h->pack.window_span = 4096;   // 4096 positions x 4 columns x 4 B = 64 KiB of LDS
   h->pack.window_tile_rows = (int32_t)env_int("ARROW_WINDOW_TILE_ROWS", h->pack.window_tile_rows);
+  h->pack.window_level_share = (double)env_int("ARROW_WINDOW_SHARE_X1000", (int64_t)(h->pack.window_level_share * 1000)) / 1000.0;
   h->pack.window_reuse = (double)env_int("ARROW_WINDOW_REUSE_X10", (int64_t)(h->pack.window_reuse * 10)) / 10.0;
   h->tuning.l2_resident_bytes = env_int("ARROW_L2_RESIDENT_BYTES", h->tuning.l2_resident_bytes);
   h->tuning.kc = (int32_t)env_int("ARROW_KC", 0);

@@ -118,15 +118,17 @@ __global__ __launch_bounds__(kBlock) void rows_kernel(
     float* __restrict__ partials, int k, int accumulate) {
   using V = typename Vec<VEC>::type;
   constexpr int GPB = kBlock / LPR;             // lane groups per workgroup
-  constexpr int UU = U < LPR ? U : LPR;         // never read past the group's own strip slots
-  __shared__ Entry strip[kBlock];
+  // entries a lane group parks in LDS per batch: four loads per lane, between 8 and 64 entries
+  constexpr int SG = 4 * LPR < 8 ? 8 : (4 * LPR > 64 ? 64 : 4 * LPR);
+  constexpr int UU = U < SG ? U : SG;
+  __shared__ Entry strip[GPB * SG];
   const int tid = threadIdx.x;
   const int l = tid % LPR;
   const int c = l * VEC + blockIdx.y * (LPR * VEC);
   const bool col_ok = c < k;
   const uint32_t row_bytes = 4u * (uint32_t)k;
   const uint32_t col_bytes = col_ok ? 4u * (uint32_t)c : 0u;   // lanes past the last column read column 0
-  const Entry* grp = strip + (tid - l);         // the group's LPR slots
+  Entry* grp = strip + (tid / LPR) * SG;        // the group's SG slots
   const int64_t first = (int64_t)blockIdx.x * kItemsPerGroupBlock;
   for (int it = tid / LPR; it < kItemsPerGroupBlock; it += GPB) {
     const int64_t r = first + it;
@@ -137,27 +139,32 @@ __global__ __launch_bounds__(kBlock) void rows_kernel(
     const uint32_t mid = rows_mid[r];
     const uint32_t hi = rows_ptr[r + 1];
     V acc = vzero<VEC>();
-    for (int seg = 0; seg < 2; ++seg) {
-      const char* base = reinterpret_cast<const char*>(seg == 0 ? Xh : X);
-      const uint32_t s_lo = seg == 0 ? lo : mid;
-      const uint32_t s_hi = seg == 0 ? mid : hi;
-      for (uint32_t b0 = s_lo; b0 < s_hi; b0 += LPR) {
-        const uint32_t nb = s_hi - b0 < (uint32_t)LPR ? s_hi - b0 : (uint32_t)LPR;
-        if ((uint32_t)l < nb) strip[tid] = ent[b0 + l];
-        strip_sync();
-        for (uint32_t j = 0; j < nb; j += UU) {
+    for (uint32_t b0 = lo; b0 < hi; b0 += SG) {
+      const uint32_t nb = hi - b0 < (uint32_t)SG ? hi - b0 : (uint32_t)SG;
+#pragma unroll
+      for (int t = 0; t < SG / LPR; ++t) {
+        const uint32_t idx = (uint32_t)(l + t * LPR);
+        if (idx < nb) grp[idx] = ent[b0 + idx];
+      }
+      strip_sync();
+      // entries [0, ns) of the batch read the staged head buffer, [ns, nb) read X
+      const uint32_t ns = mid > b0 ? (mid - b0 < nb ? mid - b0 : nb) : 0u;
+      for (int seg = 0; seg < 2; ++seg) {
+        const char* base = reinterpret_cast<const char*>(seg == 0 ? Xh : X);
+        const uint32_t j_hi = seg == 0 ? ns : nb;
+        for (uint32_t j = seg == 0 ? 0u : ns; j < j_hi; j += UU) {
           Entry e[UU];
           V x[UU];
 #pragma unroll
-          for (int u = 0; u < UU; ++u) e[u] = grp[(j + u) % LPR];
+          for (int u = 0; u < UU; ++u) e[u] = grp[(j + u) % SG];
 #pragma unroll
           for (int u = 0; u < UU; ++u)
-            x[u] = (j + u < nb) ? load_row<VEC, SMALL>(base, e[u].xrow, row_bytes, col_bytes) : vzero<VEC>();
+            x[u] = (j + u < j_hi) ? load_row<VEC, SMALL>(base, e[u].xrow, row_bytes, col_bytes) : vzero<VEC>();
 #pragma unroll
-          for (int u = 0; u < UU; ++u) vfma(acc, (j + u < nb) ? e[u].val : 0.f, x[u]);
+          for (int u = 0; u < UU; ++u) vfma(acc, (j + u < j_hi) ? e[u].val : 0.f, x[u]);
         }
-        strip_sync();
       }
+      strip_sync();
     }
     if (col_ok) {
       if (dst >= 0) {

@@ -189,13 +189,23 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
             t.row_end = (uint32_t)P.wrow_pos.size();
             if (t.row_end > t.row_begin) {
               P.wtiles.push_back(t);
-              if ((int64_t)t.win_count > img.max_window_span) img.max_window_span = t.win_count;
             }
           }
           p0 = p1;
         }
       }
+      // a separate launch for a handful of tiles costs more than it saves: keep the tiles only
+      // when they hold a fair share of the level
+      if ((double)nnz_w < opt.window_level_share * (double)lev_nnz) {
+        std::fill(taken.begin(), taken.end(), 0);
+        P.wtiles.clear();
+        P.wrow_pos.clear();
+        nnz_w = 0;
+      }
     }
+
+    for (const WindowTile& t : P.wtiles)
+      if ((int64_t)t.win_count > img.max_window_span) img.max_window_span = t.win_count;
 
     // ---- short rows / long rows -------------------------------------------------------------
     for (int64_t p = 0; p < L.n_i; ++p) {

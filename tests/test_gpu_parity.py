@@ -171,6 +171,7 @@ def test_lds_window_on_a_later_level_accumulates(torch, monkeypatch):
     band is cut at block boundaries, so later levels own banded diagonal blocks and must add."""
     monkeypatch.setenv("ARROW_SEPARATORS", "0")
     monkeypatch.setenv("ARROW_WINDOW_REUSE_X10", "5")
+    monkeypatch.setenv("ARROW_WINDOW_SHARE_X1000", "0")
     rng = np.random.default_rng(12)
     n, b, k = 6000, 500, 20
     rows, cols = [], []
