@@ -205,7 +205,7 @@ int arrow_self_check(const arrow_handle *h);
  * contiguous buffer before the product), ARROW_WINDOW_SPAN (widest column span of a diagonal-block tile whose
  * window of P_i X is staged in LDS, default 2048, at most 4096, 0 = no such tiles),
  * ARROW_WINDOW_TILE_ROWS (most rows per tile, default 1024), ARROW_WINDOW_REUSE_X10 (a tile is
- * kept when its diagonal-block entries number at least this / 10 times its span, default 20),
+ * kept when its diagonal-block entries number at least this / 10 times its span, default 80),
  * ARROW_WINDOW_SHARE_X1000 (the tiles of a level are kept when they hold at least this / 1000 of
  * the level's entries, default 50),
  * ARROW_SEPARATORS and ARROW_BFS_TAIL (0 disables the separator rule / the breadth-first

@@ -102,7 +102,7 @@ struct PackOptions {
   int32_t stage_head = 1;     // gather the head rows of level 0 into a contiguous buffer
   int32_t window_span = 2048; // widest column span of an LDS-window tile (0 = no such tiles)
   int32_t window_tile_rows = 1024;  // most rows per tile
-  double window_reuse = 2.0;  // a tile is kept when its diagonal-block entries >= this x span
+  double window_reuse = 8.0;  // a tile is kept when its diagonal-block entries >= this x span
   double window_level_share = 0.05;  // ... and the tiles of a level when they hold this share of its entries
 };
 

@@ -268,14 +268,16 @@ __global__ __launch_bounds__(kBlock) void chunks_kernel(
 // and every diagonal-block entry of the tile's rows then reads its X row from LDS; the rows'
 // first-block-column entries read X_0 rows from memory.  One lane group per row.
 // ---------------------------------------------------------------------------
+constexpr int kWinBlock = 1024;   // threads of a window-kernel workgroup: 16 wavefronts share one staged window
+
 template <int VEC, int LPR>
-__global__ __launch_bounds__(kBlock) void window_kernel(
+__global__ __launch_bounds__(kWinBlock) void window_kernel(
     const WindowTile* __restrict__ tiles, const uint32_t* __restrict__ wrow_ptr,
     const uint32_t* __restrict__ wrow_mid, const int32_t* __restrict__ wrow_y,
     const Entry* __restrict__ ent, const int32_t* __restrict__ perm, const float* __restrict__ X,
     float* __restrict__ Y, int k, int accumulate) {
   using V = typename Vec<VEC>::type;
-  constexpr int GPB = kBlock / LPR;
+  constexpr int GPB = kWinBlock / LPR;
   constexpr int W = LPR * VEC;                       // columns per slice = LDS row length
   extern __shared__ float win[];                     // win_count x W floats
   const WindowTile t = tiles[blockIdx.x];
@@ -283,25 +285,47 @@ __global__ __launch_bounds__(kBlock) void window_kernel(
   const int grp = threadIdx.x / LPR;
   const int c = l * VEC + blockIdx.y * W;
   const bool col_ok = c < k;
-  // stage: lane group j loads window rows j, j + GPB, ...
-  for (uint32_t i = grp; i < t.win_count; i += GPB) {
-    V v = vzero<VEC>();
-    if (col_ok) v = vload<VEC>(X + (size_t)perm[t.win_begin + i] * (size_t)k + c);
-    vstore<VEC>(win + (size_t)i * W + l * VEC, v);
+  const float* Xc = X + (col_ok ? c : 0);
+  // stage: lane group j loads window rows j, j + GPB, ... four at a time
+  for (uint32_t i0 = grp; i0 < t.win_count; i0 += 4 * GPB) {
+    int32_t src[4];
+    V v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t i = i0 + u * GPB;
+      src[u] = i < t.win_count ? perm[t.win_begin + i] : -1;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      v[u] = (src[u] >= 0 && col_ok) ? vload<VEC>(Xc + (size_t)src[u] * (size_t)k) : vzero<VEC>();
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const uint32_t i = i0 + u * GPB;
+      if (i < t.win_count) vstore<VEC>(win + (size_t)i * W + l * VEC, v[u]);
+    }
   }
   __syncthreads();
   for (uint32_t wr = t.row_begin + grp; wr < t.row_end; wr += GPB) {
     const uint32_t lo = wrow_ptr[wr], mid = wrow_mid[wr], hi = wrow_ptr[wr + 1];
     V acc = vzero<VEC>();
-    if (col_ok) {
-      for (uint32_t j = lo; j < mid; ++j) {          // first block column: X_0 rows from memory
-        const Entry e = ent[j];
-        vfma(acc, e.val, vload<VEC>(X + (size_t)e.xrow * (size_t)k + c));
-      }
+    for (uint32_t j = lo; j < mid; j += 4) {         // first block column: X_0 rows from memory
+      Entry e[4];
+      V x[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) e[u] = ent[j + u < mid ? j + u : lo];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        x[u] = (j + u < mid) ? vload<VEC>(Xc + (size_t)e[u].xrow * (size_t)k) : vzero<VEC>();
+#pragma unroll
+      for (int u = 0; u < 4; ++u) vfma(acc, (j + u < mid) ? e[u].val : 0.f, x[u]);
     }
-    for (uint32_t j = mid; j < hi; ++j) {            // diagonal block: rows of the LDS window
-      const Entry e = ent[j];
-      vfma(acc, e.val, vload<VEC>(win + (size_t)e.xrow * W + l * VEC));
+    for (uint32_t j = mid; j < hi; j += 4) {         // diagonal block: rows of the LDS window
+      Entry e[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) e[u] = ent[j + u < hi ? j + u : mid];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (j + u < hi) vfma(acc, e[u].val, vload<VEC>(win + (size_t)e[u].xrow * W + l * VEC));
     }
     if (col_ok) {
       float* y = Y + (size_t)wrow_y[wr] * (size_t)k + c;
@@ -501,7 +525,7 @@ int launch_window(const WindowTile* tiles, int64_t n_tiles, int64_t max_span, co
     if (n_tiles > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
     dim3 grid((unsigned)n_tiles, (unsigned)s.slices);
     const size_t lds = (size_t)max_span * LPR * VEC * sizeof(float);
-    hipLaunchKernelGGL((window_kernel<VEC, LPR>), grid, dim3(kBlock), lds, (hipStream_t)stream, tiles,
+    hipLaunchKernelGGL((window_kernel<VEC, LPR>), grid, dim3(kWinBlock), lds, (hipStream_t)stream, tiles,
                        wrow_ptr, wrow_mid, wrow_y, entries, perm, X, Y, (int)k, accumulate ? 1 : 0);
     return (int)hipGetLastError();
   });

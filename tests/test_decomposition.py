@@ -211,6 +211,7 @@ def test_error_paths():
     dict(ARROW_WINDOW_ROWS="0", ARROW_CHUNK_NNZ="7", ARROW_SHORT_MAX="3"),
     dict(ARROW_WINDOW_ROWS="64", ARROW_CHUNK_MIN="5", ARROW_CHUNK_NNZ="40"),
     dict(ARROW_WINDOW_SPAN="0"), dict(ARROW_WINDOW_SPAN="4096", ARROW_WINDOW_REUSE_X10="1"),
+    dict(ARROW_WINDOW_REUSE_X10="20", ARROW_WINDOW_SHARE_X1000="0"),
 ])
 def test_packed_image_self_check_under_pack_options(monkeypatch, env):
     for name, v in env.items():

@@ -154,14 +154,39 @@ def test_grid_one_level(torch):
 
 
 @pytest.mark.parametrize("k", [4, 7, 32, 36, 130])
-def test_diagonal_blocks_with_lds_window(torch, k):
-    """Grid operator: the stencil sits in the diagonal blocks, whose X window is staged in LDS."""
+def test_diagonal_blocks_with_lds_window(torch, monkeypatch, k):
+    """Grid operator: the stencil sits in the diagonal blocks, whose X window is staged in LDS
+    (the reuse threshold is lowered: by default a five-point stencil is left to the L2)."""
+    monkeypatch.setenv("ARROW_WINDOW_REUSE_X10", "20")
     w = synth.make_config(1, shrink=6)              # 128 x 128 grid
     X = synth.normal_matrix(w.n, k, seed=40 + k)
     op, _, Y = run_product(torch, csr_of(w), 2048, X)
     lv = op.levels()
     assert lv[0]["window_tiles"] > 0 and lv[0]["nnz_window"] > 0.5 * w.nnz
     Yref, B = oracle.spmm(*csr_of(w), X)
+    assert_within(Y, Yref, B)
+    op.close()
+
+
+def test_dense_diagonal_blocks_use_lds_window_by_default(torch):
+    """Block-diagonal operand with 24 entries per row inside blocks of 256: every block's window
+    is reused 24 times, which the default rule accepts."""
+    rng = np.random.default_rng(21)
+    n, b, k = 8192, 256, 36
+    rows = np.repeat(np.arange(n), 24)
+    cols = (rows // b) * b + rng.integers(0, b, rows.shape[0])
+    key = np.unique(rows.astype(np.int64) * n + cols)
+    rows, cols = key // n, key % n
+    rowptr = np.zeros(n + 1, np.int64)
+    np.add.at(rowptr, rows + 1, 1)
+    rowptr = np.cumsum(rowptr)
+    colidx = cols.astype(np.int32)
+    vals = synth.fill_uniform(rowptr, colidx, seed=22)
+    X = synth.normal_matrix(n, k, seed=23)
+    op, _, Y = run_product(torch, (rowptr, colidx, vals), b, X)
+    lv = op.levels()
+    assert lv[0]["window_tiles"] >= n // b - 1 and lv[0]["nnz_window"] > 0.9 * len(vals)
+    Yref, B = oracle.spmm(rowptr, colidx, vals, X)
     assert_within(Y, Yref, B)
     op.close()
 
