@@ -225,6 +225,19 @@ int arrow_get_profile(arrow_handle *h, arrow_profile_t *out);
  * the whole product). */
 int arrow_get_level_profile(arrow_handle *h, int32_t level, arrow_profile_t *out);
 
+/*
+ * Persistence (host only).  arrow_save writes the arrow matrices of a handle (permutations and
+ * the entries of every B_i, not the device image) to `path`; arrow_load reads such a file, checks
+ * it (sizes, injective permutations, ordered in-range column positions, arrow shape of width b,
+ * entry count) and rebuilds the device image with the pack-time choices of the CURRENT
+ * environment, so a decomposition is paid once per operand.  The loaded handle behaves like one
+ * from arrow_decompose (it still needs arrow_upload and a workspace).
+ * Errors: EINVAL (NULL, file cannot be opened / written, not a level file, truncated, fails a
+ * check), ENOMEM.
+ */
+int arrow_save(const arrow_handle *h, const char *path);
+int arrow_load(const char *path, arrow_handle **out);
+
 /* Thread-local text of the last error ("" if none). Never NULL. */
 const char *arrow_last_error(void);
 

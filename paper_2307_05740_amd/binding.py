@@ -24,7 +24,8 @@ EXPORTED = [
     "arrow_decompose", "arrow_device_bytes", "arrow_upload", "arrow_workspace_bytes",
     "arrow_set_workspace", "arrow_spmm", "arrow_spmm_iter", "arrow_gather", "arrow_info",
     "arrow_level_info", "arrow_export_level", "arrow_self_check", "arrow_set_option", "arrow_set_profiling",
-    "arrow_get_profile", "arrow_get_level_profile", "arrow_last_error", "arrow_destroy",
+    "arrow_get_profile", "arrow_get_level_profile", "arrow_save", "arrow_load", "arrow_last_error",
+    "arrow_destroy",
 ]
 
 
@@ -99,6 +100,10 @@ def lib():
     L.arrow_get_profile.argtypes = [vp, ctypes.POINTER(arrow_profile_t)]
     L.arrow_get_level_profile.restype = ctypes.c_int
     L.arrow_get_level_profile.argtypes = [vp, i32, ctypes.POINTER(arrow_profile_t)]
+    L.arrow_save.restype = ctypes.c_int
+    L.arrow_save.argtypes = [vp, ctypes.c_char_p]
+    L.arrow_load.restype = ctypes.c_int
+    L.arrow_load.argtypes = [ctypes.c_char_p, ctypes.POINTER(vp)]
     L.arrow_last_error.restype = ctypes.c_char_p
     L.arrow_last_error.argtypes = []
     L.arrow_destroy.restype = None
@@ -205,6 +210,16 @@ def arrow_get_level_profile(h: int, level: int) -> dict:
     return {f: getattr(out, f) for f, _ in out._fields_}
 
 
+def arrow_save(h: int, path: str) -> None:
+    _check(lib().arrow_save(h, os.fsencode(path)))
+
+
+def arrow_load(path: str) -> int:
+    out = ctypes.c_void_p()
+    _check(lib().arrow_load(os.fsencode(path), ctypes.byref(out)))
+    return out.value
+
+
 def arrow_destroy(h: int) -> None:
     lib().arrow_destroy(h)
 
@@ -212,11 +227,11 @@ def arrow_destroy(h: int) -> None:
 class ArrowSpMM:
     """One decomposed operand bound to torch-owned device memory (plumbing only)."""
 
-    def __init__(self, rowptr, colidx, vals, b: int, device="cuda:0"):
+    def __init__(self, rowptr=None, colidx=None, vals=None, b: int = 0, device="cuda:0", handle=None):
         import torch
         self._torch = torch
         self.device = torch.device(device)
-        self.h = arrow_decompose(rowptr, colidx, vals, b)
+        self.h = handle if handle is not None else arrow_decompose(rowptr, colidx, vals, b)
         self.info = arrow_info(self.h)
         self.n = self.info["n"]
         nbytes = arrow_device_bytes(self.h)

@@ -180,6 +180,26 @@ int product(arrow_handle* h, const float* X, float* Y, int32_t k, hipStream_t st
   return ARROW_OK;
 }
 
+// pack-time and launch-time choices from the environment (see arrow_set_option in arrow.h)
+void read_pack_options(arrow_handle* h) {
+  h->pack.short_max = (int32_t)env_int("ARROW_SHORT_MAX", h->pack.short_max);
+  h->pack.chunk_nnz = (int32_t)env_int("ARROW_CHUNK_NNZ", h->pack.chunk_nnz);
+  h->pack.chunk_min = (int32_t)env_int("ARROW_CHUNK_MIN", h->pack.chunk_min);
+  h->pack.window_rows = (int32_t)env_int("ARROW_WINDOW_ROWS", h->pack.window_rows);
+  h->pack.classes = (int32_t)env_int("ARROW_CLASSES", h->pack.classes);
+  h->pack.class_gran = (int32_t)env_int("ARROW_CLASS_GRAN", h->pack.class_gran);
+  h->pack.class_min = (int32_t)env_int("ARROW_CLASS_MIN", h->pack.class_min);
+  h->pack.piece_max = (int32_t)env_int("ARROW_PIECE_MAX", h->pack.piece_max);
+  h->pack.stage_head = (int32_t)env_int("ARROW_STAGE_HEAD", h->pack.stage_head);
+  h->pack.window_span = (int32_t)env_int("ARROW_WINDOW_SPAN", h->pack.window_span);
+  if (h->pack.window_span > 4096) h->pack.window_span = 4096;   // 4096 positions x 4 columns x 4 B = 64 KiB of LDS
+  h->pack.window_tile_rows = (int32_t)env_int("ARROW_WINDOW_TILE_ROWS", h->pack.window_tile_rows);
+  h->pack.window_level_share = (double)env_int("ARROW_WINDOW_SHARE_X1000", (int64_t)(h->pack.window_level_share * 1000)) / 1000.0;
+  h->pack.window_reuse = (double)env_int("ARROW_WINDOW_REUSE_X10", (int64_t)(h->pack.window_reuse * 10)) / 10.0;
+  h->tuning.l2_resident_bytes = env_int("ARROW_L2_RESIDENT_BYTES", h->tuning.l2_resident_bytes);
+  h->tuning.kc = (int32_t)env_int("ARROW_KC", 0);
+}
+
 int ready(const arrow_handle* h, int32_t k, bool need_iter_buffer) {
   if (!h) return fail(ARROW_EINVAL, "handle is NULL");
   if (k < 1) return fail(ARROW_EINVAL, "k must be >= 1 (got %d)", k);
@@ -192,6 +212,49 @@ int ready(const arrow_handle* h, int32_t k, bool need_iter_buffer) {
   return ARROW_OK;
 }
 
+}  // namespace
+
+// ---- persistence: the levels are written, the device image is rebuilt on load -----------------
+namespace {
+constexpr char kFileMagic[8] = {'A', 'R', 'R', 'O', 'W', 'L', 'V', '1'};
+constexpr char kFileEnd[8] = {'A', 'R', 'R', 'O', 'W', 'E', 'N', 'D'};
+
+template <typename T>
+bool put(FILE* f, const T* p, size_t cnt) { return cnt == 0 || std::fwrite(p, sizeof(T), cnt, f) == cnt; }
+template <typename T>
+bool get(FILE* f, T* p, size_t cnt) { return cnt == 0 || std::fread(p, sizeof(T), cnt, f) == cnt; }
+
+// structural validity of levels read from a file (everything the kernels later rely on)
+bool levels_valid(int64_t n, int64_t nnz, int32_t b, const std::vector<arrow::HostLevel>& levels,
+                  std::string& why) {
+  int64_t total = 0;
+  std::vector<uint8_t> seen(n);
+  for (size_t li = 0; li < levels.size(); ++li) {
+    const arrow::HostLevel& L = levels[li];
+    if (L.n_i < 0 || L.n_i > n || (li == 0 && L.n_i != n)) { why = "bad level size"; return false; }
+    if ((int64_t)L.perm.size() != L.n_i || (int64_t)L.rowptr.size() != L.n_i + 1) { why = "bad array sizes"; return false; }
+    std::fill(seen.begin(), seen.end(), 0);
+    for (int64_t p = 0; p < L.n_i; ++p) {
+      const int32_t v = L.perm[p];
+      if (v < 0 || v >= n || seen[v]) { why = "perm is not an injection into [0, n)"; return false; }
+      seen[v] = 1;
+    }
+    if (L.rowptr[0] != 0) { why = "rowptr[0] != 0"; return false; }
+    const int64_t lev_nnz = L.rowptr[L.n_i];
+    if (lev_nnz < 0 || (int64_t)L.colpos.size() != lev_nnz || (int64_t)L.vals.size() != lev_nnz) { why = "bad entry arrays"; return false; }
+    for (int64_t p = 0; p < L.n_i; ++p) {
+      if (L.rowptr[p] > L.rowptr[p + 1] || L.rowptr[p + 1] > lev_nnz) { why = "rowptr not monotone"; return false; }
+      for (int64_t e = L.rowptr[p]; e < L.rowptr[p + 1]; ++e) {
+        const int64_t q = L.colpos[e];
+        if (q < 0 || q >= L.n_i || (e > L.rowptr[p] && L.colpos[e - 1] >= q)) { why = "column positions out of range or unordered"; return false; }
+        if (!(p < b || q < b || p / b == q / b)) { why = "an entry lies outside the arrow shape"; return false; }
+      }
+    }
+    total += lev_nnz;
+  }
+  if (total != nnz) { why = "entry count differs from the header"; return false; }
+  return true;
+}
 }  // namespace
 
 extern "C" {
@@ -233,22 +296,7 @@ int arrow_decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, con
   arrow::DecomposeOptions dopt;
   dopt.separators = env_int("ARROW_SEPARATORS", 1) != 0;
   dopt.bfs_tail = env_int("ARROW_BFS_TAIL", 1) != 0;
-  h->pack.short_max = (int32_t)env_int("ARROW_SHORT_MAX", h->pack.short_max);
-  h->pack.chunk_nnz = (int32_t)env_int("ARROW_CHUNK_NNZ", h->pack.chunk_nnz);
-  h->pack.chunk_min = (int32_t)env_int("ARROW_CHUNK_MIN", h->pack.chunk_min);
-  h->pack.window_rows = (int32_t)env_int("ARROW_WINDOW_ROWS", h->pack.window_rows);
-  h->pack.classes = (int32_t)env_int("ARROW_CLASSES", h->pack.classes);
-  h->pack.class_gran = (int32_t)env_int("ARROW_CLASS_GRAN", h->pack.class_gran);
-  h->pack.class_min = (int32_t)env_int("ARROW_CLASS_MIN", h->pack.class_min);
-  h->pack.piece_max = (int32_t)env_int("ARROW_PIECE_MAX", h->pack.piece_max);
-  h->pack.stage_head = (int32_t)env_int("ARROW_STAGE_HEAD", h->pack.stage_head);
-  h->pack.window_span = (int32_t)env_int("ARROW_WINDOW_SPAN", h->pack.window_span);
-  if (h->pack.window_span > 4096) h->pack.window_span = 4096;   // 4096 positions x 4 columns x 4 B = 64 KiB of LDS
-  h->pack.window_tile_rows = (int32_t)env_int("ARROW_WINDOW_TILE_ROWS", h->pack.window_tile_rows);
-  h->pack.window_level_share = (double)env_int("ARROW_WINDOW_SHARE_X1000", (int64_t)(h->pack.window_level_share * 1000)) / 1000.0;
-  h->pack.window_reuse = (double)env_int("ARROW_WINDOW_REUSE_X10", (int64_t)(h->pack.window_reuse * 10)) / 10.0;
-  h->tuning.l2_resident_bytes = env_int("ARROW_L2_RESIDENT_BYTES", h->tuning.l2_resident_bytes);
-  h->tuning.kc = (int32_t)env_int("ARROW_KC", 0);
+  read_pack_options(h);
   std::string err;
   int rc;
   try {
@@ -441,6 +489,82 @@ int arrow_get_level_profile(arrow_handle* h, int32_t level, arrow_profile_t* out
   }
   e = hipEventElapsedTime(&out->total_ms, h->spans[0].a, h->spans[h->spans_used - 1].b);
   if (e != hipSuccess) return check_hip((int)e, "event elapsed time");
+  return ARROW_OK;
+}
+
+int arrow_save(const arrow_handle* h, const char* path) {
+  if (!h || !path) return fail(ARROW_EINVAL, "NULL argument");
+  FILE* f = std::fopen(path, "wb");
+  if (!f) return fail(ARROW_EINVAL, "cannot open '%s' for writing", path);
+  const uint32_t version = 1;
+  const int32_t n_levels = (int32_t)h->levels.size();
+  bool ok = put(f, kFileMagic, 8) && put(f, &version, 1) && put(f, &h->n, 1) && put(f, &h->nnz, 1) &&
+            put(f, &h->b, 1) && put(f, &n_levels, 1);
+  for (const arrow::HostLevel& L : h->levels) {
+    if (!ok) break;
+    const int64_t lev_nnz = L.rowptr[L.n_i];
+    const int64_t stats[4] = {L.nnz_head_head, L.nnz_head_row, L.nnz_head_col, L.nnz_diag};
+    const int32_t sep = L.separator_rule ? 1 : 0;
+    ok = put(f, &L.n_i, 1) && put(f, &lev_nnz, 1) && put(f, stats, 4) && put(f, &sep, 1) &&
+         put(f, L.perm.data(), (size_t)L.n_i) && put(f, L.rowptr.data(), (size_t)L.n_i + 1) &&
+         put(f, L.colpos.data(), (size_t)lev_nnz) && put(f, L.vals.data(), (size_t)lev_nnz);
+  }
+  ok = ok && put(f, kFileEnd, 8);
+  if (std::fclose(f) != 0) ok = false;
+  if (!ok) return fail(ARROW_EINVAL, "writing '%s' failed", path);
+  return ARROW_OK;
+}
+
+int arrow_load(const char* path, arrow_handle** out) {
+  if (!out) return fail(ARROW_EINVAL, "out is NULL");
+  *out = nullptr;
+  if (!path) return fail(ARROW_EINVAL, "path is NULL");
+  FILE* f = std::fopen(path, "rb");
+  if (!f) return fail(ARROW_EINVAL, "cannot open '%s'", path);
+  arrow_handle* h = new (std::nothrow) arrow_handle;
+  if (!h) { std::fclose(f); return fail(ARROW_ENOMEM, "out of host memory"); }
+  char magic[8];
+  uint32_t version = 0;
+  int32_t n_levels = 0;
+  std::string why;
+  bool ok = get(f, magic, 8) && std::memcmp(magic, kFileMagic, 8) == 0 && get(f, &version, 1) &&
+            version == 1 && get(f, &h->n, 1) && get(f, &h->nnz, 1) && get(f, &h->b, 1) && get(f, &n_levels, 1);
+  if (ok && (h->n < 1 || h->n > 2147483646LL || h->b < 1 || h->nnz < 0 || h->nnz >= 0xffffffffLL ||
+             n_levels < 1 || n_levels > 1000000)) ok = false;
+  if (!ok) why = "not an arrow level file (bad header)";
+  try {
+    for (int32_t li = 0; ok && li < n_levels; ++li) {
+      arrow::HostLevel L;
+      int64_t lev_nnz = 0, stats[4];
+      int32_t sep = 0;
+      ok = get(f, &L.n_i, 1) && get(f, &lev_nnz, 1) && get(f, stats, 4) && get(f, &sep, 1) &&
+           L.n_i >= 0 && L.n_i <= h->n && lev_nnz >= 0 && lev_nnz <= h->nnz;
+      if (!ok) { why = "truncated or corrupt level header"; break; }
+      L.perm.resize(L.n_i); L.rowptr.resize(L.n_i + 1); L.colpos.resize(lev_nnz); L.vals.resize(lev_nnz);
+      ok = get(f, L.perm.data(), (size_t)L.n_i) && get(f, L.rowptr.data(), (size_t)L.n_i + 1) &&
+           get(f, L.colpos.data(), (size_t)lev_nnz) && get(f, L.vals.data(), (size_t)lev_nnz);
+      if (!ok) { why = "truncated level data"; break; }
+      L.nnz_head_head = stats[0]; L.nnz_head_row = stats[1]; L.nnz_head_col = stats[2]; L.nnz_diag = stats[3];
+      L.separator_rule = sep != 0;
+      h->levels.push_back(std::move(L));
+    }
+    if (ok) { ok = get(f, magic, 8) && std::memcmp(magic, kFileEnd, 8) == 0; if (!ok) why = "missing end marker"; }
+    std::fclose(f);
+    f = nullptr;
+    if (ok) ok = levels_valid(h->n, h->nnz, h->b, h->levels, why);
+    if (!ok) { delete h; return fail(ARROW_EINVAL, "'%s': %s", path, why.c_str()); }
+    read_pack_options(h);
+    std::string err;
+    auto t0 = std::chrono::steady_clock::now();
+    int rc = arrow::pack_image(h->n, h->b, h->levels, h->pack, h->img, err);
+    h->decompose_seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+    if (rc != ARROW_OK) { delete h; return fail(rc, "%s", err.c_str()); }
+  } catch (const std::bad_alloc&) {
+    if (f) std::fclose(f);
+    delete h;
+    return fail(ARROW_ENOMEM, "out of host memory while loading '%s'", path);
+  }
+  *out = h;
   return ARROW_OK;
 }
 

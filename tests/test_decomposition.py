@@ -225,6 +225,49 @@ def test_packed_image_self_check_under_pack_options(monkeypatch, env):
             binding.arrow_destroy(h)
 
 
+def test_save_and_load_round_trip(tmp_path, monkeypatch):
+    w = synth.make_config(2, shrink=8)
+    h = binding.arrow_decompose(w.rowptr, w.colidx, w.vals, w.b)
+    path = str(tmp_path / "levels.arrow")
+    binding.arrow_save(h, path)
+    monkeypatch.setenv("ARROW_CHUNK_NNZ", "32")          # the image is rebuilt with the loader's choices
+    g = binding.arrow_load(path)
+    try:
+        ia, ib = binding.arrow_info(h), binding.arrow_info(g)
+        assert (ia["n"], ia["nnz"], ia["b"], ia["levels"]) == (ib["n"], ib["nnz"], ib["b"], ib["levels"])
+        for i in range(ia["levels"]):
+            for x, y in zip(binding.arrow_export_level(h, i), binding.arrow_export_level(g, i)):
+                assert np.array_equal(x.view(np.uint32) if x.dtype == np.float32 else x,
+                                      y.view(np.uint32) if y.dtype == np.float32 else y)
+        binding.arrow_self_check(g)
+        assert binding.arrow_level_info(g, 0)["chunks"] >= binding.arrow_level_info(h, 0)["chunks"]
+    finally:
+        binding.arrow_destroy(h)
+        binding.arrow_destroy(g)
+    # damaged files are refused, never half-loaded
+    raw = open(path, "rb").read()
+    bad = tmp_path / "bad.arrow"
+    for blob in (raw[:len(raw) // 2], b"NOTARROW" + raw[8:], raw[:-8] + b"XXXXXXXX", b""):
+        bad.write_bytes(blob)
+        with pytest.raises(binding.ArrowError) as ei:
+            binding.arrow_load(str(bad))
+        assert ei.value.code == binding.ARROW_EINVAL
+    # a column position outside the level fails the structural check
+    levels_off = 8 + 4 + 8 + 8 + 4 + 4
+    n_i = int(np.frombuffer(raw, np.int64, 1, levels_off)[0])
+    lev_nnz = int(np.frombuffer(raw, np.int64, 1, levels_off + 8)[0])
+    col_off = levels_off + 8 + 8 + 32 + 4 + 4 * n_i + 8 * (n_i + 1)
+    cols = np.frombuffer(raw, np.int32, lev_nnz, col_off).copy()
+    cols[-1] = n_i                                        # a column position outside the level
+    blob = bytearray(raw)
+    blob[col_off:col_off + 4 * lev_nnz] = cols.tobytes()
+    bad.write_bytes(bytes(blob))
+    with pytest.raises(binding.ArrowError):
+        binding.arrow_load(str(bad))
+    with pytest.raises(binding.ArrowError):
+        binding.arrow_load(str(tmp_path / "does_not_exist"))
+
+
 def test_library_exports_every_declared_symbol():
     import re
     header = open(os.path.join(os.path.dirname(_build.REPO_DIR + "/x"), "include", "arrow.h")).read()

@@ -311,6 +311,18 @@ def test_grid_eigenvector_powers(torch):
     op.close()
 
 
+def test_loaded_handle_gives_the_same_product(torch, tmp_path):
+    w = synth.make_config(3, shrink=8)
+    X = w.make_x()
+    op, Xd, Y = run_product(torch, csr_of(w), w.b, X)
+    path = str(tmp_path / "levels.arrow")
+    binding.arrow_save(op.h, path)
+    op2 = binding.ArrowSpMM(handle=binding.arrow_load(path))
+    Y2 = op2.spmm(Xd).cpu().numpy()
+    assert np.array_equal(Y.view(np.uint32), Y2.view(np.uint32))   # same image, same order of sums
+    op.close(); op2.close()
+
+
 def test_errors_on_device(torch):
     w = synth.make_config(0, shrink=3)
     op = binding.ArrowSpMM(*csr_of(w), w.b)
