@@ -4,7 +4,7 @@ Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
 ``bench.py`` may import this package.  It shares no code with the GPU library
 and imports nothing from it.
 
-* :func:`spmm`, :func:`spmm_iter` -- ctypes wrappers of ``spmm_oracle.c``
+* :func:`spmm`, :func:`spmm_iter`, :func:`sddmm` -- ctypes wrappers of ``spmm_oracle.c``
   (plain CSR loops in fp64 over the original, undecomposed operand).
 * :mod:`oracle.arrow_checks` -- host-side checks of a decomposition
   (bit-exact reassembly, arrow shape, injective permutations) and a slow
@@ -34,6 +34,8 @@ def _load():
         lib.oracle_spmm.argtypes = [i64, vp, vp, vp, vp, i64, i32, i64, vp, vp, vp]
         lib.oracle_spmm_iter.restype = ctypes.c_int
         lib.oracle_spmm_iter.argtypes = [i64, vp, vp, vp, vp, i32, i32, vp, vp]
+        lib.oracle_sddmm.restype = ctypes.c_int
+        lib.oracle_sddmm.argtypes = [i64, vp, vp, vp, vp, vp, i32, vp, vp]
         lib.oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -89,6 +91,24 @@ def spmm_iter(rowptr, colidx, vals, X, l: int):
     if rc != 0:
         raise RuntimeError(f"oracle_spmm_iter failed ({rc})")
     return Xl, El
+
+
+def sddmm(rowptr, colidx, vals, U, V):
+    """fp64 ``S[p] = a_p * <U[i,:], V[j,:]>`` on the pattern of A (CSR order) and its bound
+    ``|a_p| * <|U[i,:]|, |V[j,:]|>``.  Returns ``(S, B)``, float64 arrays of length nnz."""
+    rowptr, colidx, vals = _csr(rowptr, colidx, vals)
+    n = rowptr.shape[0] - 1
+    for M in (U, V):
+        assert M.dtype == np.float32 and M.ndim == 2 and M.flags.c_contiguous and M.shape[0] == n
+    assert U.shape == V.shape
+    nnz = int(rowptr[-1])
+    S = np.empty(nnz, dtype=np.float64)
+    B = np.empty(nnz, dtype=np.float64)
+    rc = _load().oracle_sddmm(n, rowptr.ctypes.data, colidx.ctypes.data, vals.ctypes.data,
+                              U.ctypes.data, V.ctypes.data, U.shape[1], S.ctypes.data, B.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"oracle_sddmm failed ({rc})")
+    return S, B
 
 
 def num_threads() -> int:

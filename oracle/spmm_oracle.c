@@ -22,6 +22,8 @@
  * Rows are independent, so the OpenMP loop over rows changes no summation
  * order.  No blocking, fusion or reordering.
  *
+ * The file also holds the sampled dense-dense product on the same pattern (oracle_sddmm).
+ *
  * Pins (tests/test_oracle_pins.py): dense brute force, identity /
  * permutation / diagonal operands, unit-vector columns, row-stochastic
  * operand times ones, grid operator times ones and its sine eigenvectors
@@ -107,6 +109,37 @@ int oracle_spmm_iter(int64_t n, const int64_t *rowptr, const int32_t *colidx,
     memcpy(El, En, (size_t)tot * sizeof(double));
   }
   free(Xn); free(En);
+  return 0;
+}
+
+/*
+ * Sampled dense-dense product on the pattern of A (the order-2 case of the paper's TTTP kernel,
+ * section "Tensor Decomposition and Completion Algorithms", with the third mode dropped; the
+ * output has the sparsity of the sparse operand, section "SpTTN Kernels"):
+ *   S[p] = vals[p] * sum_r U[i, r] * V[j, r]        for the nonzero p = (i, j) of A,
+ *   B[p] = |vals[p]| * sum_r |U[i, r]| * |V[j, r]|   (the bound the tolerance is scaled by),
+ * in CSR order of A, fp64 accumulation over r in increasing order.  U, V: n x k fp32 row-major.
+ * Returns 0, or -1 on bad arguments.
+ */
+int oracle_sddmm(int64_t n, const int64_t *rowptr, const int32_t *colidx, const float *vals,
+                 const float *U, const float *V, int32_t k, double *S, double *B) {
+  if (n < 0 || !rowptr || (!colidx && rowptr[n] > 0) || (!vals && rowptr[n] > 0) || !U || !V ||
+      k < 1 || !S || !B)
+    return -1;
+#pragma omp parallel for schedule(dynamic, 64)
+  for (int64_t i = 0; i < n; ++i) {
+    const float *u = U + i * (int64_t)k;
+    for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) {
+      const float *v = V + (int64_t)colidx[p] * k;
+      double dot = 0.0, adot = 0.0;
+      for (int32_t r = 0; r < k; ++r) {
+        dot += (double)u[r] * (double)v[r];
+        adot += fabs((double)u[r]) * fabs((double)v[r]);
+      }
+      S[p] = (double)vals[p] * dot;
+      B[p] = fabs((double)vals[p]) * adot;
+    }
+  }
   return 0;
 }
 

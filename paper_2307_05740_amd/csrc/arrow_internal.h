@@ -16,6 +16,7 @@ struct HostLevel {
   std::vector<int64_t> rowptr;     // n_i + 1
   std::vector<int32_t> colpos;     // column positions, ascending inside a row
   std::vector<float> vals;
+  std::vector<uint32_t> src;       // index of every entry in the caller's CSR arrays
   int64_t nnz_head_head = 0, nnz_head_row = 0, nnz_head_col = 0, nnz_diag = 0;
   bool separator_rule = false;
 };
@@ -62,11 +63,13 @@ struct LevelImage {
   size_t off_rows_ptr = 0;   // uint32 n_rows + 1 (offsets into the level's entry array)
   size_t off_rows_mid = 0;   // uint32 n_rows : entries before it read the staged head buffer, the rest read X
   size_t off_rows_dst = 0;   // int32  n_rows : >= 0 -> Y row, < 0 -> partial slot (-1 - slot), INT32_MIN -> padding
+  size_t off_rows_row = 0;   // int32  n_rows : the vertex (row of A) the item belongs to, -1 for padding
   // wave list: items handled one per wavefront (the list may contain empty padding slots)
   int64_t n_chunks = 0, n_real_chunks = 0, chunks_partials = 0, nnz_chunks = 0;
   size_t off_chunk_ptr = 0;  // uint32 n_chunks + 1
   size_t off_chunk_mid = 0;  // uint32 n_chunks : entries before it read the staged head buffer, the rest read X
   size_t off_chunk_dst = 0;  // int32  n_chunks : >= 0 -> Y row (whole row in one chunk), < 0 -> partial slot (-1 - slot)
+  size_t off_chunk_row = 0;  // int32  n_chunks : the vertex the item belongs to, -1 for padding
   // rows assembled from several chunks
   int64_t n_split = 0, n_partials = 0;
   size_t off_split_ptr = 0;  // uint32 n_split + 1 (partial slots of a row are consecutive)
@@ -81,6 +84,8 @@ struct LevelImage {
   size_t off_wrow_ptr = 0;   // uint32 n_wrows + 1
   size_t off_wrow_mid = 0;   // uint32 n_wrows : entries before it read X rows, the rest index the LDS window
   size_t off_wrow_y = 0;     // int32  n_wrows
+  size_t off_wrow_win = 0;   // uint32 n_wrows : first position of the row's tile window
+  int64_t map_offset = 0;    // first element of this level in the entry map (one uint32 per entry, image order)
 };
 
 // Rows [row_begin, row_end) of the window-row list belong to one diagonal block and touch only
@@ -100,6 +105,7 @@ struct PackOptions {
   int32_t class_min = 32;     // a row is split by class when it holds classes * class_min entries
   int32_t piece_max = 48;     // a class piece with at most this many entries is a group-list item
   int32_t stage_head = 1;     // gather the head rows of level 0 into a contiguous buffer
+  bool build_entry_map = false;  // also produce Image::entry_src (needed by the sampled product only)
   int32_t window_span = 2048; // widest column span of an LDS-window tile (0 = no such tiles)
   int32_t window_tile_rows = 1024;  // most rows per tile
   double window_reuse = 8.0;  // a tile is kept when its diagonal-block entries >= this x span
@@ -112,6 +118,7 @@ struct Image {
   int64_t max_partials = 0;
   int64_t max_stage_rows = 0;
   int64_t max_window_span = 0;
+  std::vector<uint32_t> entry_src;   // per entry in image order: its index in the caller's CSR arrays (optional)
 };
 
 int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const PackOptions& opt,

@@ -43,6 +43,8 @@ struct Remainder {
   std::vector<int64_t> own_ptr;
   std::vector<int32_t> own_col;
   std::vector<float> own_val;
+  const uint32_t* src = nullptr;     // index of every entry in the caller's CSR arrays (NULL: identity)
+  std::vector<uint32_t> own_src;
   int64_t nnz(int64_t n) const { return ptr[n]; }
 };
 
@@ -284,8 +286,10 @@ int decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const flo
     if (lev_nnz == 0 && rem_nnz > 0) { err = "a level captured no entry"; return ARROW_EINTERNAL; }
     L.colpos.resize(lev_nnz);
     L.vals.resize(lev_nnz);
+    L.src.resize(lev_nnz);
     std::vector<int32_t> next_col(next_nnz);
     std::vector<float> next_val(next_nnz);
+    std::vector<uint32_t> next_src(next_nnz);
     int64_t hh = 0, hr = 0, hc = 0, dg = 0;
 #pragma omp parallel for schedule(dynamic, 1024) reduction(+ : hh, hr, hc, dg)
     for (int64_t u = 0; u < n; ++u) {
@@ -298,11 +302,13 @@ int decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const flo
         if (in_arrow(pu, pv)) {
           L.colpos[w] = (int32_t)pv;
           L.vals[w] = R.val[p];
+          L.src[w] = R.src ? R.src[p] : (uint32_t)p;
           ++w;
           if (pu < b) { if (pv < b) ++hh; else ++hr; } else { if (pv < b) ++hc; else ++dg; }
         } else {
           next_col[x] = R.col[p];
           next_val[x] = R.val[p];
+          next_src[x] = R.src ? R.src[p] : (uint32_t)p;
           ++x;
         }
       }
@@ -313,16 +319,19 @@ int decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const flo
         for (int64_t q = w0 + 1; q < w; ++q) if (L.colpos[q - 1] > L.colpos[q]) { sorted = false; break; }
         if (!sorted) {
           std::vector<uint64_t> key(len);
-          for (int64_t q = 0; q < len; ++q) {
-            uint32_t bits;
-            std::memcpy(&bits, &L.vals[w0 + q], 4);
-            key[q] = ((uint64_t)(uint32_t)L.colpos[w0 + q] << 32) | bits;
-          }
+          for (int64_t q = 0; q < len; ++q) key[q] = ((uint64_t)(uint32_t)L.colpos[w0 + q] << 32) | (uint64_t)q;
           std::sort(key.begin(), key.end());
+          std::vector<float> tv(len);
+          std::vector<uint32_t> ts(len);
+          for (int64_t q = 0; q < len; ++q) {
+            const int64_t from = w0 + (int64_t)(key[q] & 0xffffffffu);
+            tv[q] = L.vals[from];
+            ts[q] = L.src[from];
+          }
           for (int64_t q = 0; q < len; ++q) {
             L.colpos[w0 + q] = (int32_t)(key[q] >> 32);
-            uint32_t bits = (uint32_t)key[q];
-            std::memcpy(&L.vals[w0 + q], &bits, 4);
+            L.vals[w0 + q] = tv[q];
+            L.src[w0 + q] = ts[q];
           }
         }
       }
@@ -333,7 +342,8 @@ int decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const flo
     R.own_ptr.swap(next_ptr);
     R.own_col.swap(next_col);
     R.own_val.swap(next_val);
-    R.ptr = R.own_ptr.data(); R.col = R.own_col.data(); R.val = R.own_val.data();
+    R.own_src.swap(next_src);
+    R.ptr = R.own_ptr.data(); R.col = R.own_col.data(); R.val = R.own_val.data(); R.src = R.own_src.data();
     if (next_nnz == 0) break;
   }
   return ARROW_OK;

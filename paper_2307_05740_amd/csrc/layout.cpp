@@ -70,6 +70,7 @@ struct Plan {
   std::vector<uint32_t> slot_of;      // rec seq -> slot in its list
   std::vector<uint32_t> list_ptr[2];  // per list: entry offsets, slots + 1
   std::vector<int32_t> list_dst[2];   // per list: destination per slot
+  std::vector<int32_t> list_row[2];   // per list: the Y row (vertex) the item belongs to, -1 for padding
   int64_t piece_slots = 0;            // group-list slots before the plain short rows
   std::vector<uint32_t> split_ptr;
   std::vector<int32_t> split_y;
@@ -137,6 +138,7 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
 
   std::vector<Plan> plans(levels.size());
   size_t total = 0;
+  int64_t map_total = 0;     // entries of all levels: the entry map is one uint32 per entry
 
   for (size_t li = 0; li < levels.size(); ++li) {
     const HostLevel& L = levels[li];
@@ -328,17 +330,21 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
           order_list(P.recs, list, class_phases, list == 0 ? kItemsPerGroupBlock : kChunksPerGroup);
       std::vector<uint32_t>& ptr = P.list_ptr[list];
       std::vector<int32_t>& dst = P.list_dst[list];
+      std::vector<int32_t>& irow = P.list_row[list];
       ptr.reserve(fin.size() + (list == 0 ? P.row_pos.size() : 0) + 1);
       dst.reserve(fin.size() + (list == 0 ? P.row_pos.size() : 0));
+      irow.reserve(fin.size() + (list == 0 ? P.row_pos.size() : 0));
       const int64_t at0 = at;
       for (size_t s = 0; s < fin.size(); ++s) {
         ptr.push_back((uint32_t)at);
         if (fin[s] == kPad) {
           dst.push_back(INT32_MIN);                  // padding slot: no entries, no output
+          irow.push_back(-1);
         } else {
           const Rec& rc = P.recs[fin[s]];
           P.slot_of[rc.seq] = (uint32_t)s;
           dst.push_back(rc.dst);
+          irow.push_back(L.perm[rc.row]);
           at += rc.len;
           ++real_items[list];
           if (rc.dst < 0) ++part_items[list];
@@ -349,6 +355,7 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
         for (int32_t p : P.row_pos) {                // plain short rows follow the class pieces
           ptr.push_back((uint32_t)at);
           dst.push_back(L.perm[p]);
+          irow.push_back(L.perm[p]);
           at += L.rowptr[p + 1] - L.rowptr[p];
           ++real_items[0];
         }
@@ -397,21 +404,27 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
     im.off_rows_ptr = total;    total = align_up(total + sizeof(uint32_t) * (size_t)(im.n_rows + 1));
     im.off_rows_mid = total;    total = align_up(total + sizeof(uint32_t) * (size_t)im.n_rows);
     im.off_rows_dst = total;    total = align_up(total + sizeof(int32_t) * (size_t)im.n_rows);
+    im.off_rows_row = total;    total = align_up(total + sizeof(int32_t) * (size_t)im.n_rows);
     im.off_chunk_ptr = total;   total = align_up(total + sizeof(uint32_t) * (size_t)(im.n_chunks + 1));
     im.off_chunk_mid = total;   total = align_up(total + sizeof(uint32_t) * (size_t)im.n_chunks);
     im.off_chunk_dst = total;   total = align_up(total + sizeof(int32_t) * (size_t)im.n_chunks);
+    im.off_chunk_row = total;   total = align_up(total + sizeof(int32_t) * (size_t)im.n_chunks);
     im.off_split_ptr = total;   total = align_up(total + sizeof(uint32_t) * (size_t)(im.n_split + 1));
     im.off_split_y = total;     total = align_up(total + sizeof(int32_t) * (size_t)im.n_split);
     im.off_wtiles = total;      total = align_up(total + sizeof(WindowTile) * (size_t)im.n_wtiles);
     im.off_wrow_ptr = total;    total = align_up(total + sizeof(uint32_t) * (size_t)(im.n_wrows + 1));
     im.off_wrow_mid = total;    total = align_up(total + sizeof(uint32_t) * (size_t)im.n_wrows);
     im.off_wrow_y = total;      total = align_up(total + sizeof(int32_t) * (size_t)im.n_wrows);
+    im.off_wrow_win = total;    total = align_up(total + sizeof(uint32_t) * (size_t)im.n_wrows);
     im.off_entries = total;     total = align_up(total + sizeof(Entry) * (size_t)lev_nnz);
+    im.map_offset = map_total;  map_total += lev_nnz;
     img.levels.push_back(im);
   }
 
   try {
     img.bytes.assign(total, 0);
+    img.entry_src.clear();
+    if (opt.build_entry_map) img.entry_src.assign((size_t)map_total, 0);
   } catch (const std::bad_alloc&) {
     err = "out of host memory while packing the image";
     return ARROW_ENOMEM;
@@ -427,6 +440,9 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
     std::memcpy(base + im.off_chunk_ptr, P.list_ptr[1].data(), sizeof(uint32_t) * P.list_ptr[1].size());
     if (im.n_rows) std::memcpy(base + im.off_rows_dst, P.list_dst[0].data(), sizeof(int32_t) * (size_t)im.n_rows);
     if (im.n_chunks) std::memcpy(base + im.off_chunk_dst, P.list_dst[1].data(), sizeof(int32_t) * (size_t)im.n_chunks);
+    if (im.n_rows) std::memcpy(base + im.off_rows_row, P.list_row[0].data(), sizeof(int32_t) * (size_t)im.n_rows);
+    if (im.n_chunks) std::memcpy(base + im.off_chunk_row, P.list_row[1].data(), sizeof(int32_t) * (size_t)im.n_chunks);
+    uint32_t* emap = opt.build_entry_map ? img.entry_src.data() + im.map_offset : nullptr;
     std::memcpy(base + im.off_split_ptr, P.split_ptr.data(), sizeof(uint32_t) * P.split_ptr.size());
     if (!P.split_y.empty())
       std::memcpy(base + im.off_split_y, P.split_y.data(), sizeof(int32_t) * P.split_y.size());
@@ -462,6 +478,7 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
       for (uint32_t e = P.list_ptr[0][slot]; e < P.list_ptr[0][slot + 1]; ++e, ++src) {
         ent[e].xrow = L.perm[L.colpos[src]];
         ent[e].val = L.vals[src];
+        if (emap) emap[e] = L.src[src];
       }
     }
     // long rows: items in emission order
@@ -504,6 +521,7 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
               ent[e_out].xrow = L.perm[q];
             }
             ent[e_out].val = L.vals[src0 + e];
+            if (emap) emap[e_out] = L.src[src0 + e];
           }
           list_mid[list][slot] = P.list_ptr[list][slot] + staged_here;
         }
@@ -516,6 +534,7 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
       std::memcpy(base + im.off_wrow_ptr, P.wrow_ptr.data(), sizeof(uint32_t) * P.wrow_ptr.size());
       uint32_t* wmid = reinterpret_cast<uint32_t*>(base + im.off_wrow_mid);
       int32_t* wy = reinterpret_cast<int32_t*>(base + im.off_wrow_y);
+      uint32_t* wwin = reinterpret_cast<uint32_t*>(base + im.off_wrow_win);
       const int64_t n_tiles = im.n_wtiles;
 #pragma omp parallel for schedule(dynamic, 4)
       for (int64_t t = 0; t < n_tiles; ++t) {
@@ -523,6 +542,7 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
         for (uint32_t wr = T.row_begin; wr < T.row_end; ++wr) {
           const int32_t p = P.wrow_pos[wr];
           wy[wr] = L.perm[p];
+          wwin[wr] = T.win_begin;
           int64_t src = L.rowptr[p];
           uint32_t e = P.wrow_ptr[wr];
           uint32_t mid = e;
@@ -531,6 +551,7 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
             if (q < b) { ent[e].xrow = L.perm[q]; mid = e + 1; }
             else ent[e].xrow = q - (int32_t)T.win_begin;
             ent[e].val = L.vals[src];
+            if (emap) emap[e] = L.src[src];
           }
           wmid[wr] = mid;
         }

@@ -203,3 +203,73 @@ def test_linearity_and_symmetry_identities():
     Xs = (2.0 * X + X2).astype(np.float32)                  # exact? no: rounded, so use the bound
     Ys, Bs = oracle.spmm(*A, Xs)
     assert np.all(np.abs(Ys - (2 * Y + Y2)) <= 2.0 ** -22 * (2 * B + B2) + 1e-30)
+
+
+# ---------------------------------------------------------------------------------------------
+# sampled dense-dense product  S(i,j) = A(i,j) * sum_r U(i,r) V(j,r)
+# ---------------------------------------------------------------------------------------------
+def test_sddmm_exact_rational_brute_force():
+    rng = np.random.default_rng(31)
+    n, k = 19, 5
+    rowptr, colidx, vals, Vd = random_csr(rng, n, 0.3, full_row=2, full_col=3, empty_row=7)
+    U = rng.standard_normal((n, k)).astype(np.float32)
+    W = rng.standard_normal((n, k)).astype(np.float32)
+    S, B = oracle.sddmm(rowptr, colidx, vals, U, W)
+    u = 2.0 ** -53
+    p = 0
+    for i in range(n):
+        for j in range(n):
+            if Vd[i, j] == 0 and not (rowptr[i] <= p < rowptr[i + 1] and colidx[p] == j):
+                continue
+            dot = sum(Fraction(float(U[i, r])) * Fraction(float(W[j, r])) for r in range(k))
+            adot = sum(abs(Fraction(float(U[i, r])) * Fraction(float(W[j, r]))) for r in range(k))
+            a = Fraction(float(vals[p]))
+            assert colidx[p] == j
+            assert abs(Fraction(S[p]) - a * dot) <= Fraction((k + 2) * u) * abs(a) * adot
+            assert abs(Fraction(B[p]) - abs(a) * adot) <= Fraction((k + 2) * u) * abs(a) * adot
+            p += 1
+    assert p == rowptr[-1]
+
+
+def test_sddmm_hand_worked_and_transposition():
+    # A = [[0, 2], [-1, 0.5]], U = [[1, 2], [3, 4]], V = [[5, 6], [7, 8]]
+    # U V^T = [[17, 23], [39, 53]]  ->  S = [2*23, -1*39, 0.5*53] = [46, -39, 26.5]
+    rowptr = np.array([0, 1, 3], np.int64)
+    colidx = np.array([1, 0, 1], np.int32)
+    vals = np.array([2, -1, 0.5], np.float32)
+    U = np.array([[1, 2], [3, 4]], np.float32)
+    V = np.array([[5, 6], [7, 8]], np.float32)
+    S, B = oracle.sddmm(rowptr, colidx, vals, U, V)
+    assert np.array_equal(S, [46.0, -39.0, 26.5]) and np.array_equal(B, [46.0, 39.0, 26.5])
+    St, _ = oracle.sddmm(rowptr, colidx, vals, V, U)          # swapping U and V is a different product
+    # V U^T = (U V^T)^T = [[17, 39], [23, 53]]
+    assert np.array_equal(St, [2 * 39.0, -1 * 23.0, 0.5 * 53.0])
+
+
+def test_sddmm_closed_forms_and_library():
+    w = synth.make_config(0, shrink=2)
+    n, k = w.n, 7
+    A = sp.csr_matrix((w.vals.astype(np.float64), w.colidx, w.rowptr), shape=(n, n))
+    ones = np.ones((n, k), np.float32)
+    S, B = oracle.sddmm(w.rowptr, w.colidx, w.vals, ones, ones)
+    assert np.array_equal(S, k * w.vals.astype(np.float64)) and np.array_equal(B, k * np.abs(w.vals, dtype=np.float64))
+    U = synth.normal_matrix(n, k, seed=5)
+    V = synth.normal_matrix(n, k, seed=6)
+    S, B = oracle.sddmm(w.rowptr, w.colidx, w.vals, U, V)
+    D = U.astype(np.float64) @ V.astype(np.float64).T
+    rows = np.repeat(np.arange(n), np.diff(w.rowptr))
+    want = w.vals.astype(np.float64) * D[rows, w.colidx]
+    assert np.all(np.abs(S - want) <= 1e-13 * B)
+    assert np.allclose(A.multiply(D).tocsr().data, S, rtol=0, atol=1e-12)     # library: elementwise product
+    # identity operand with U = V: squared row norms; unit-vector factors pick single products
+    rp = np.arange(n + 1, dtype=np.int64)
+    Sd, _ = oracle.sddmm(rp, np.arange(n, dtype=np.int32), np.ones(n, np.float32), U, U)
+    assert np.allclose(Sd, np.sum(U.astype(np.float64) ** 2, axis=1), rtol=1e-15)
+    E = np.zeros((n, k), np.float32); E[:, 2] = 1
+    S2, _ = oracle.sddmm(w.rowptr, w.colidx, w.vals, U, E)                    # S = a_ij * U[i, 2]
+    assert np.array_equal(S2, w.vals.astype(np.float64) * U[rows, 2].astype(np.float64))
+    # consistency with the product kernel: row sums of S equal (A .* (U V^T)) 1 = diag-free identity
+    Y, _ = oracle.spmm(w.rowptr, w.colidx, w.vals, V)                         # A V
+    lhs = np.add.reduceat(np.concatenate([S, [0.0]]), np.minimum(w.rowptr[:-1], len(S)))[:n]
+    lhs[np.diff(w.rowptr) == 0] = 0.0
+    assert np.all(np.abs(lhs - np.sum(U.astype(np.float64) * Y, axis=1)) <= 1e-11 * (1 + np.abs(lhs)))
