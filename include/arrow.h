@@ -226,10 +226,35 @@ int arrow_get_profile(arrow_handle *h, arrow_profile_t *out);
 int arrow_get_level_profile(arrow_handle *h, int32_t level, arrow_profile_t *out);
 
 /*
+ * Sampled dense-dense product on the pattern of A,
+ *     S[p] = a_p * sum_r U[i, r] V[j, r]        for the nonzero p = (i, j) of A,
+ * the order-2 case of the paper's TTTP kernel (section "Tensor Decomposition and Completion
+ * Algorithms"; the output has the sparsity of the sparse operand, section "SpTTN Kernels").  It
+ * runs over the same arrow layout and work lists as the product: the rows V[j, :] are gathered
+ * exactly as the rows X[j, :] of arrow_spmm are, U[i, :] takes the place of the accumulator.
+ *
+ * The kernels need the entry map (one uint32 per nonzero: image order -> index in the caller's
+ * CSR arrays).  arrow_sddmm_device_bytes returns its size; arrow_sddmm_upload copies it to
+ * `dev_buf` (DEVICE memory, 256-byte aligned, caller-owned, must outlive every arrow_sddmm call on
+ * the handle) asynchronously on `stream`.
+ *
+ * arrow_sddmm: U, V DEVICE pointers to n x k fp32 row-major, 16-byte aligned (U == V is allowed);
+ * S DEVICE pointer to nnz fp32, written in the order of the caller's CSR arrays (every element is
+ * written exactly once, nothing is accumulated).  Needs arrow_upload, arrow_sddmm_upload and a
+ * workspace of arrow_workspace_bytes(h, k).  Launches on `stream` and returns without waiting.
+ * fp32 arithmetic, deterministic summation order.
+ * Errors: EINVAL (NULL, alignment, k < 1), ENOTREADY (no image / map / workspace), ETOOSMALL
+ * (buffer or workspace too small), EHIP.
+ */
+size_t arrow_sddmm_device_bytes(const arrow_handle *h);
+int arrow_sddmm_upload(arrow_handle *h, void *dev_buf, size_t bytes, void *stream);
+int arrow_sddmm(arrow_handle *h, const float *U, const float *V, float *S, int32_t k, void *stream);
+
+/*
  * Persistence (host only).  arrow_save writes the arrow matrices of a handle (permutations and
- * the entries of every B_i, not the device image) to `path`; arrow_load reads such a file, checks
+ * the entries of every B_i with their indices in the caller's CSR arrays, not the device image) to `path`; arrow_load reads such a file, checks
  * it (sizes, injective permutations, ordered in-range column positions, arrow shape of width b,
- * entry count) and rebuilds the device image with the pack-time choices of the CURRENT
+ * entry count, source indices a bijection onto the nonzeros) and rebuilds the device image with the pack-time choices of the CURRENT
  * environment, so a decomposition is paid once per operand.  The loaded handle behaves like one
  * from arrow_decompose (it still needs arrow_upload and a workspace).
  * Errors: EINVAL (NULL, file cannot be opened / written, not a level file, truncated, fails a

@@ -22,7 +22,8 @@ ARROW_OK, ARROW_EINVAL, ARROW_ENOMEM, ARROW_ENOTREADY, ARROW_ETOOSMALL, ARROW_EH
 
 EXPORTED = [
     "arrow_decompose", "arrow_device_bytes", "arrow_upload", "arrow_workspace_bytes",
-    "arrow_set_workspace", "arrow_spmm", "arrow_spmm_iter", "arrow_gather", "arrow_info",
+    "arrow_set_workspace", "arrow_spmm", "arrow_spmm_iter", "arrow_sddmm_device_bytes",
+    "arrow_sddmm_upload", "arrow_sddmm", "arrow_gather", "arrow_info",
     "arrow_level_info", "arrow_export_level", "arrow_self_check", "arrow_set_option", "arrow_set_profiling",
     "arrow_get_profile", "arrow_get_level_profile", "arrow_save", "arrow_load", "arrow_last_error",
     "arrow_destroy",
@@ -82,6 +83,12 @@ def lib():
     L.arrow_spmm.argtypes = [vp, vp, vp, i32, vp]
     L.arrow_spmm_iter.restype = ctypes.c_int
     L.arrow_spmm_iter.argtypes = [vp, vp, i32, i32, vp]
+    L.arrow_sddmm_device_bytes.restype = sz
+    L.arrow_sddmm_device_bytes.argtypes = [vp]
+    L.arrow_sddmm_upload.restype = ctypes.c_int
+    L.arrow_sddmm_upload.argtypes = [vp, vp, sz, vp]
+    L.arrow_sddmm.restype = ctypes.c_int
+    L.arrow_sddmm.argtypes = [vp, vp, vp, vp, i32, vp]
     L.arrow_gather.restype = ctypes.c_int
     L.arrow_gather.argtypes = [vp, i32, vp, vp, i32, vp]
     L.arrow_info.restype = ctypes.c_int
@@ -156,6 +163,18 @@ def arrow_spmm(h: int, x_ptr: int, y_ptr: int, k: int, stream: int = 0) -> None:
 
 def arrow_spmm_iter(h: int, x_ptr: int, k: int, l: int, stream: int = 0) -> None:
     _check(lib().arrow_spmm_iter(h, x_ptr, k, l, stream))
+
+
+def arrow_sddmm_device_bytes(h: int) -> int:
+    return int(lib().arrow_sddmm_device_bytes(h))
+
+
+def arrow_sddmm_upload(h: int, dev_ptr: int, nbytes: int, stream: int = 0) -> None:
+    _check(lib().arrow_sddmm_upload(h, dev_ptr, nbytes, stream))
+
+
+def arrow_sddmm(h: int, u_ptr: int, v_ptr: int, s_ptr: int, k: int, stream: int = 0) -> None:
+    _check(lib().arrow_sddmm(h, u_ptr, v_ptr, s_ptr, k, stream))
 
 
 def arrow_gather(h: int, level: int, x_ptr: int, xp_ptr: int, k: int, stream: int = 0) -> None:
@@ -241,6 +260,7 @@ class ArrowSpMM:
             torch.cuda.current_stream().synchronize()
         self._ws = None
         self._ws_k = 0
+        self._map = None
 
     def _stream(self) -> int:
         return self._torch.cuda.current_stream(self.device).cuda_stream
@@ -277,6 +297,26 @@ class ArrowSpMM:
         self._ensure_workspace(X.shape[1])
         arrow_spmm_iter(self.h, X.data_ptr(), X.shape[1], l, self._stream())
         return X
+
+    def sddmm(self, U, V, S=None):
+        """``S[p] = a_p <U[i], V[j]>`` for the nonzeros p = (i, j), in the caller's CSR order."""
+        torch = self._torch
+        for M in (U, V):
+            assert M.is_cuda and M.dtype == torch.float32 and M.dim() == 2 and M.is_contiguous()
+            assert M.shape[0] == self.n
+        assert U.shape == V.shape
+        k = U.shape[1]
+        if self._map is None:
+            nbytes = arrow_sddmm_device_bytes(self.h)
+            self._map = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
+            arrow_sddmm_upload(self.h, self._map.data_ptr(), self._map.numel(), self._stream())
+            torch.cuda.current_stream(self.device).synchronize()
+        if S is None:
+            S = torch.empty(self.info["nnz"], dtype=torch.float32, device=self.device)
+        assert S.dtype == torch.float32 and S.is_contiguous() and S.numel() == self.info["nnz"]
+        self._ensure_workspace(k)
+        arrow_sddmm(self.h, U.data_ptr(), V.data_ptr(), S.data_ptr(), k, self._stream())
+        return S
 
     def gather(self, level: int, X):
         torch = self._torch

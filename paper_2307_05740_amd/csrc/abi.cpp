@@ -64,6 +64,7 @@ struct arrow_handle {
   unsigned char* dev = nullptr;
   unsigned char* ws = nullptr;
   size_t ws_bytes = 0;
+  const uint32_t* dev_map = nullptr;   // entry map (sampled product only)
   // profiling
   bool profiling = false;
   std::vector<Span> spans;   // event pool, reused between products
@@ -180,6 +181,47 @@ int product(arrow_handle* h, const float* X, float* Y, int32_t k, hipStream_t st
   return ARROW_OK;
 }
 
+// S = A .* (U V^T) on the pattern of A, level by level; every stored entry is written once
+int sampled_product(arrow_handle* h, const float* U, const float* V, float* S, int32_t k,
+                    hipStream_t stream) {
+  float* stage = reinterpret_cast<float*>(h->ws + partial_bytes(h, k));
+  for (size_t li = 0; li < h->img.levels.size(); ++li) {
+    const arrow::LevelImage& im = h->img.levels[li];
+    const arrow::Entry* ent = at<arrow::Entry>(h, im.off_entries);
+    const uint32_t* emap = h->dev_map + im.map_offset;
+    const float* Vh = V;
+    if (im.staged) {
+      Scoped sc(h, kStage, (int)li, stream);
+      int rc = arrow::launch_gather(at<int32_t>(h, im.off_stage_perm), im.n_stage, V, stage, k, stream);
+      if (rc) return check_hip(rc, "head staging launch");
+      Vh = stage;
+    }
+    if (im.n_chunks > 0) {
+      Scoped sc(h, kChunks, (int)li, stream);
+      int rc = arrow::launch_sddmm_chunks(at<uint32_t>(h, im.off_chunk_ptr), at<uint32_t>(h, im.off_chunk_mid),
+                                          at<int32_t>(h, im.off_chunk_row), ent, emap, im.n_chunks, U, V,
+                                          h->n, Vh, S, k, stream);
+      if (rc) return check_hip(rc, "sampled chunks kernel launch");
+    }
+    if (im.n_rows > 0) {
+      Scoped sc(h, kRows, (int)li, stream);
+      int rc = arrow::launch_sddmm_rows(0, at<uint32_t>(h, im.off_rows_ptr), at<uint32_t>(h, im.off_rows_mid),
+                                        at<int32_t>(h, im.off_rows_row), nullptr, nullptr, ent, emap,
+                                        im.n_rows, U, V, h->n, Vh, S, k, stream);
+      if (rc) return check_hip(rc, "sampled rows kernel launch");
+    }
+    if (im.n_wrows > 0) {
+      Scoped sc(h, kWindow, (int)li, stream);
+      int rc = arrow::launch_sddmm_rows(1, at<uint32_t>(h, im.off_wrow_ptr), at<uint32_t>(h, im.off_wrow_mid),
+                                        at<int32_t>(h, im.off_wrow_y), at<uint32_t>(h, im.off_wrow_win),
+                                        at<int32_t>(h, im.off_perm), ent, emap, im.n_wrows, U, V, h->n,
+                                        V, S, k, stream);
+      if (rc) return check_hip(rc, "sampled window-rows kernel launch");
+    }
+  }
+  return ARROW_OK;
+}
+
 // pack-time and launch-time choices from the environment (see arrow_set_option in arrow.h)
 void read_pack_options(arrow_handle* h) {
   h->pack.short_max = (int32_t)env_int("ARROW_SHORT_MAX", h->pack.short_max);
@@ -229,6 +271,7 @@ bool levels_valid(int64_t n, int64_t nnz, int32_t b, const std::vector<arrow::Ho
                   std::string& why) {
   int64_t total = 0;
   std::vector<uint8_t> seen(n);
+  std::vector<uint8_t> used((size_t)nnz, 0);   // every nonzero of the caller's CSR belongs to one entry
   for (size_t li = 0; li < levels.size(); ++li) {
     const arrow::HostLevel& L = levels[li];
     if (L.n_i < 0 || L.n_i > n || (li == 0 && L.n_i != n)) { why = "bad level size"; return false; }
@@ -241,7 +284,8 @@ bool levels_valid(int64_t n, int64_t nnz, int32_t b, const std::vector<arrow::Ho
     }
     if (L.rowptr[0] != 0) { why = "rowptr[0] != 0"; return false; }
     const int64_t lev_nnz = L.rowptr[L.n_i];
-    if (lev_nnz < 0 || (int64_t)L.colpos.size() != lev_nnz || (int64_t)L.vals.size() != lev_nnz) { why = "bad entry arrays"; return false; }
+    if (lev_nnz < 0 || (int64_t)L.colpos.size() != lev_nnz || (int64_t)L.vals.size() != lev_nnz ||
+        (int64_t)L.src.size() != lev_nnz) { why = "bad entry arrays"; return false; }
     for (int64_t p = 0; p < L.n_i; ++p) {
       if (L.rowptr[p] > L.rowptr[p + 1] || L.rowptr[p + 1] > lev_nnz) { why = "rowptr not monotone"; return false; }
       for (int64_t e = L.rowptr[p]; e < L.rowptr[p + 1]; ++e) {
@@ -249,6 +293,11 @@ bool levels_valid(int64_t n, int64_t nnz, int32_t b, const std::vector<arrow::Ho
         if (q < 0 || q >= L.n_i || (e > L.rowptr[p] && L.colpos[e - 1] >= q)) { why = "column positions out of range or unordered"; return false; }
         if (!(p < b || q < b || p / b == q / b)) { why = "an entry lies outside the arrow shape"; return false; }
       }
+    }
+    for (int64_t e = 0; e < lev_nnz; ++e) {
+      const uint32_t s = L.src[e];
+      if ((int64_t)s >= nnz || used[s]) { why = "source indices are not a bijection onto the nonzeros"; return false; }
+      used[s] = 1;
     }
     total += lev_nnz;
   }
@@ -381,6 +430,36 @@ int arrow_spmm_iter(arrow_handle* h, float* X, int32_t k, int32_t l, void* strea
   return ARROW_OK;
 }
 
+size_t arrow_sddmm_device_bytes(const arrow_handle* h) {
+  return h ? align_up(sizeof(uint32_t) * (h->img.entry_src.size() + 1)) : 0;
+}
+
+int arrow_sddmm_upload(arrow_handle* h, void* dev_buf, size_t bytes, void* stream) {
+  if (!h) return fail(ARROW_EINVAL, "handle is NULL");
+  if (!dev_buf) return fail(ARROW_EINVAL, "dev_buf is NULL");
+  if ((uintptr_t)dev_buf % kAlign) return fail(ARROW_EINVAL, "dev_buf must be 256-byte aligned");
+  const size_t need = sizeof(uint32_t) * h->img.entry_src.size();
+  if (bytes < need) return fail(ARROW_ETOOSMALL, "entry map needs %zu bytes, buffer has %zu", need, bytes);
+  if (need) {
+    hipError_t e = hipMemcpyAsync(dev_buf, h->img.entry_src.data(), need, hipMemcpyHostToDevice,
+                                  (hipStream_t)stream);
+    if (e != hipSuccess) return check_hip((int)e, "entry map upload");
+  }
+  h->dev_map = static_cast<const uint32_t*>(dev_buf);
+  return ARROW_OK;
+}
+
+int arrow_sddmm(arrow_handle* h, const float* U, const float* V, float* S, int32_t k, void* stream) {
+  int rc = ready(h, k, false);
+  if (rc) return rc;
+  if (!h->dev_map) return fail(ARROW_ENOTREADY, "arrow_sddmm_upload has not been called");
+  if (!U || !V || (!S && h->nnz > 0)) return fail(ARROW_EINVAL, "U, V or S is NULL");
+  if (((uintptr_t)U | (uintptr_t)V) % 16) return fail(ARROW_EINVAL, "U and V must be 16-byte aligned");
+  if ((uintptr_t)S % 4) return fail(ARROW_EINVAL, "S must be 4-byte aligned");
+  h->spans_used = 0;
+  return sampled_product(h, U, V, S, k, (hipStream_t)stream);
+}
+
 int arrow_gather(arrow_handle* h, int32_t level, const float* X, float* Xp, int32_t k, void* stream) {
   if (!h) return fail(ARROW_EINVAL, "handle is NULL");
   if (level < 0 || (size_t)level >= h->img.levels.size()) return fail(ARROW_EINVAL, "no level %d", level);
@@ -496,7 +575,7 @@ int arrow_save(const arrow_handle* h, const char* path) {
   if (!h || !path) return fail(ARROW_EINVAL, "NULL argument");
   FILE* f = std::fopen(path, "wb");
   if (!f) return fail(ARROW_EINVAL, "cannot open '%s' for writing", path);
-  const uint32_t version = 1;
+  const uint32_t version = 2;
   const int32_t n_levels = (int32_t)h->levels.size();
   bool ok = put(f, kFileMagic, 8) && put(f, &version, 1) && put(f, &h->n, 1) && put(f, &h->nnz, 1) &&
             put(f, &h->b, 1) && put(f, &n_levels, 1);
@@ -507,7 +586,8 @@ int arrow_save(const arrow_handle* h, const char* path) {
     const int32_t sep = L.separator_rule ? 1 : 0;
     ok = put(f, &L.n_i, 1) && put(f, &lev_nnz, 1) && put(f, stats, 4) && put(f, &sep, 1) &&
          put(f, L.perm.data(), (size_t)L.n_i) && put(f, L.rowptr.data(), (size_t)L.n_i + 1) &&
-         put(f, L.colpos.data(), (size_t)lev_nnz) && put(f, L.vals.data(), (size_t)lev_nnz);
+         put(f, L.colpos.data(), (size_t)lev_nnz) && put(f, L.vals.data(), (size_t)lev_nnz) &&
+         put(f, L.src.data(), (size_t)lev_nnz);
   }
   ok = ok && put(f, kFileEnd, 8);
   if (std::fclose(f) != 0) ok = false;
@@ -528,7 +608,7 @@ int arrow_load(const char* path, arrow_handle** out) {
   int32_t n_levels = 0;
   std::string why;
   bool ok = get(f, magic, 8) && std::memcmp(magic, kFileMagic, 8) == 0 && get(f, &version, 1) &&
-            version == 1 && get(f, &h->n, 1) && get(f, &h->nnz, 1) && get(f, &h->b, 1) && get(f, &n_levels, 1);
+            version == 2 && get(f, &h->n, 1) && get(f, &h->nnz, 1) && get(f, &h->b, 1) && get(f, &n_levels, 1);
   if (ok && (h->n < 1 || h->n > 2147483646LL || h->b < 1 || h->nnz < 0 || h->nnz >= 0xffffffffLL ||
              n_levels < 1 || n_levels > 1000000)) ok = false;
   if (!ok) why = "not an arrow level file (bad header)";
@@ -541,8 +621,10 @@ int arrow_load(const char* path, arrow_handle** out) {
            L.n_i >= 0 && L.n_i <= h->n && lev_nnz >= 0 && lev_nnz <= h->nnz;
       if (!ok) { why = "truncated or corrupt level header"; break; }
       L.perm.resize(L.n_i); L.rowptr.resize(L.n_i + 1); L.colpos.resize(lev_nnz); L.vals.resize(lev_nnz);
+      L.src.resize(lev_nnz);
       ok = get(f, L.perm.data(), (size_t)L.n_i) && get(f, L.rowptr.data(), (size_t)L.n_i + 1) &&
-           get(f, L.colpos.data(), (size_t)lev_nnz) && get(f, L.vals.data(), (size_t)lev_nnz);
+           get(f, L.colpos.data(), (size_t)lev_nnz) && get(f, L.vals.data(), (size_t)lev_nnz) &&
+           get(f, L.src.data(), (size_t)lev_nnz);
       if (!ok) { why = "truncated level data"; break; }
       L.nnz_head_head = stats[0]; L.nnz_head_row = stats[1]; L.nnz_head_col = stats[2]; L.nnz_diag = stats[3];
       L.separator_rule = sep != 0;

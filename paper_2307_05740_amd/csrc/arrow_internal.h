@@ -105,7 +105,6 @@ struct PackOptions {
   int32_t class_min = 32;     // a row is split by class when it holds classes * class_min entries
   int32_t piece_max = 48;     // a class piece with at most this many entries is a group-list item
   int32_t stage_head = 1;     // gather the head rows of level 0 into a contiguous buffer
-  bool build_entry_map = false;  // also produce Image::entry_src (needed by the sampled product only)
   int32_t window_span = 2048; // widest column span of an LDS-window tile (0 = no such tiles)
   int32_t window_tile_rows = 1024;  // most rows per tile
   double window_reuse = 8.0;  // a tile is kept when its diagonal-block entries >= this x span
@@ -118,7 +117,7 @@ struct Image {
   int64_t max_partials = 0;
   int64_t max_stage_rows = 0;
   int64_t max_window_span = 0;
-  std::vector<uint32_t> entry_src;   // per entry in image order: its index in the caller's CSR arrays (optional)
+  std::vector<uint32_t> entry_src;   // per entry in image order: its index in the caller's CSR arrays
 };
 
 int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const PackOptions& opt,
@@ -154,5 +153,19 @@ int launch_window(const WindowTile* tiles, int64_t n_tiles, int64_t max_span, co
                   const uint32_t* wrow_mid, const int32_t* wrow_y, const Entry* entries,
                   const int32_t* perm, const float* X, float* Y, int32_t k, bool accumulate,
                   void* stream);
+
+
+// Sampled dense-dense product S[emap[e]] = a_e <U[row(e)], V[col(e)]> over one work list.
+// mode 0: a group list (item_win and perm unused); mode 1: the window-row list.  emap points at the
+// level's slice of the entry map; v_rows = rows of V.
+int launch_sddmm_rows(int mode, const uint32_t* item_ptr, const uint32_t* item_mid,
+                      const int32_t* item_row, const uint32_t* item_win, const int32_t* perm,
+                      const Entry* entries, const uint32_t* emap, int64_t n_items, const float* U,
+                      const float* V, int64_t v_rows, const float* Vh, float* S, int32_t k,
+                      void* stream);
+int launch_sddmm_chunks(const uint32_t* chunk_ptr, const uint32_t* chunk_mid, const int32_t* chunk_row,
+                        const Entry* entries, const uint32_t* emap, int64_t n_chunks, const float* U,
+                        const float* V, int64_t v_rows, const float* Vh, float* S, int32_t k,
+                        void* stream);
 
 }  // namespace arrow

@@ -335,6 +335,189 @@ __global__ __launch_bounds__(kWinBlock) void window_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------
+// Sampled dense-dense product on the arrow layout:
+//     S[src(e)] = a_e * <U[i, :], V[j, :]>       for every stored entry e = (i, j).
+// It walks the same work lists as the product kernels.  Per entry the LPR lanes of a group hold
+// partial dot products of their VEC columns; NB entries are reduced together by a transposing
+// butterfly (each exchange halves the number of live values per lane), so an entry costs about
+// one cross-lane exchange instead of log2(LPR).  After the reduction lane l of the group holds the
+// dot product of entry l / (LPR / NB) of the batch.  All k columns are covered inside the kernel
+// (a loop over column slices of LPR * VEC), so the result needs no second pass.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float vdot(float u, float x) { return u * x; }
+__device__ __forceinline__ float vdot(float2 u, float2 x) { return fmaf(u.y, x.y, u.x * x.x); }
+__device__ __forceinline__ float vdot(float4 u, float4 x) {
+  return fmaf(u.w, x.w, fmaf(u.z, x.z, fmaf(u.y, x.y, u.x * x.x)));
+}
+
+template <int NB, int LPR>
+__device__ __forceinline__ float group_reduce(float (&p)[NB], int l) {
+  int m = LPR / 2;
+#pragma unroll
+  for (int n = NB; n > 1; n >>= 1) {
+    const int half = n / 2;
+    const bool upper = (l & m) != 0;          // upper lanes keep the upper half of the entries
+#pragma unroll
+    for (int e = 0; e < half; ++e) {
+      const float send = upper ? p[e] : p[e + half];
+      const float keep = upper ? p[e + half] : p[e];
+      p[e] = keep + __shfl_xor(send, m, 64);
+    }
+    m >>= 1;
+  }
+#pragma unroll
+  for (; m >= 1; m >>= 1) p[0] += __shfl_xor(p[0], m, 64);
+  return p[0];
+}
+
+// Lane group per item of a group list (MODE 0: entries before `mid` read the staged head rows
+// Vh, the rest rows of V) or per row of the window-row list (MODE 1: entries before `mid` name
+// rows of V, the rest positions inside the row's tile window, translated through perm).
+template <int VEC, int LPR, int NB, bool SMALL, int MODE>
+__global__ __launch_bounds__(kBlock) void sddmm_rows_kernel(
+    const uint32_t* __restrict__ item_ptr, const uint32_t* __restrict__ item_mid,
+    const int32_t* __restrict__ item_row, const uint32_t* __restrict__ item_win,
+    const int32_t* __restrict__ perm, const Entry* __restrict__ ent,
+    const uint32_t* __restrict__ emap, int64_t n_items, const float* __restrict__ U,
+    const float* __restrict__ Vm, const float* __restrict__ Vh, float* __restrict__ S, int k,
+    int slices) {
+  using V = typename Vec<VEC>::type;
+  constexpr int GPB = kBlock / LPR;
+  constexpr int SG = 4 * LPR < 8 ? 8 : (4 * LPR > 64 ? 64 : 4 * LPR);
+  constexpr int W = LPR * VEC;
+  constexpr int SPAN = LPR / NB;                 // lanes that end up with the same entry's sum
+  __shared__ Entry strip[GPB * SG];
+  const int tid = threadIdx.x;
+  const int l = tid % LPR;
+  const uint32_t row_bytes = 4u * (uint32_t)k;
+  Entry* grp = strip + (tid / LPR) * SG;
+  const int64_t first = (int64_t)blockIdx.x * kItemsPerGroupBlock;
+  for (int it = tid / LPR; it < kItemsPerGroupBlock; it += GPB) {
+    const int64_t r = first + it;
+    if (r >= n_items) break;
+    const int32_t row = item_row[r];
+    if (row < 0) continue;                       // padding slot of the die queues
+    const uint32_t lo = item_ptr[r];
+    const uint32_t mid = item_mid[r];
+    const uint32_t hi = item_ptr[r + 1];
+    const uint32_t win = MODE == 1 ? item_win[r] : 0u;
+    const float* Urow = U + (size_t)row * (size_t)k;
+    const V u0 = l * VEC < k ? vload<VEC>(Urow + l * VEC) : vzero<VEC>();
+    for (uint32_t b0 = lo; b0 < hi; b0 += SG) {
+      const uint32_t nb = hi - b0 < (uint32_t)SG ? hi - b0 : (uint32_t)SG;
+#pragma unroll
+      for (int t = 0; t < SG / LPR; ++t) {
+        const uint32_t idx = (uint32_t)(l + t * LPR);
+        if (idx < nb) {
+          Entry e = ent[b0 + idx];
+          if (MODE == 1 && b0 + idx >= mid) e.xrow = perm[win + (uint32_t)e.xrow];
+          grp[idx] = e;
+        }
+      }
+      strip_sync();
+      const uint32_t ns = MODE == 1 ? 0u : (mid > b0 ? (mid - b0 < nb ? mid - b0 : nb) : 0u);
+      for (int seg = 0; seg < 2; ++seg) {
+        const char* base = reinterpret_cast<const char*>(seg == 0 ? Vh : Vm);
+        const uint32_t j_hi = seg == 0 ? ns : nb;
+        for (uint32_t j = seg == 0 ? 0u : ns; j < j_hi; j += NB) {
+          int32_t xr[NB];
+          float p[NB];
+#pragma unroll
+          for (int u = 0; u < NB; ++u) { xr[u] = grp[(j + u) % SG].xrow; p[u] = 0.f; }
+          for (int sl = 0; sl < slices; ++sl) {
+            const int c = l * VEC + sl * W;
+            const bool col_ok = c < k;
+            const uint32_t col_bytes = col_ok ? 4u * (uint32_t)c : 0u;
+            const V uu = sl == 0 ? u0 : (col_ok ? vload<VEC>(Urow + c) : vzero<VEC>());
+            V x[NB];
+#pragma unroll
+            for (int u = 0; u < NB; ++u)
+              x[u] = (j + u < j_hi && col_ok) ? load_row<VEC, SMALL>(base, xr[u], row_bytes, col_bytes)
+                                              : vzero<VEC>();
+#pragma unroll
+            for (int u = 0; u < NB; ++u) p[u] += vdot(uu, x[u]);
+          }
+          const float dot = group_reduce<NB, LPR>(p, l);
+          const uint32_t mine = j + (uint32_t)(l / SPAN);
+          if (l % SPAN == 0 && mine < j_hi) S[emap[b0 + mine]] = grp[mine % SG].val * dot;
+        }
+      }
+      strip_sync();
+    }
+  }
+}
+
+// Wavefront per item of a wave list: the G lane groups take the item's entries round-robin, NB
+// rounds at a time; nothing is combined across lane groups.
+template <int VEC, int LPR, int NB, bool SMALL>
+__global__ __launch_bounds__(kBlock) void sddmm_chunks_kernel(
+    const uint32_t* __restrict__ chunk_ptr, const uint32_t* __restrict__ chunk_mid,
+    const int32_t* __restrict__ chunk_row, const Entry* __restrict__ ent,
+    const uint32_t* __restrict__ emap, int64_t n_chunks, const float* __restrict__ U,
+    const float* __restrict__ Vm, const float* __restrict__ Vh, float* __restrict__ S, int k,
+    int slices) {
+  using V = typename Vec<VEC>::type;
+  constexpr int G = 64 / LPR;
+  constexpr int WPB = kBlock / 64;
+  constexpr int W = LPR * VEC;
+  constexpr int SPAN = LPR / NB;
+  __shared__ Entry strip[WPB][64];
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / 64));
+  const int64_t ch = (int64_t)blockIdx.x * WPB + wave;
+  if (ch >= n_chunks) return;
+  const uint32_t lo = chunk_ptr[ch];
+  const uint32_t hi = chunk_ptr[ch + 1];
+  if (lo == hi) return;                          // padding slot of the die queues
+  const uint32_t mid = chunk_mid[ch];
+  const int32_t row = chunk_row[ch];
+  const int lane = threadIdx.x % 64;
+  const int g = lane / LPR;
+  const int l = lane % LPR;
+  const uint32_t row_bytes = 4u * (uint32_t)k;
+  const float* Urow = U + (size_t)row * (size_t)k;
+  const V u0 = l * VEC < k ? vload<VEC>(Urow + l * VEC) : vzero<VEC>();
+  Entry* mine = strip[wave];
+  for (int seg = 0; seg < 2; ++seg) {
+    const char* base = reinterpret_cast<const char*>(seg == 0 ? Vh : Vm);
+    const uint32_t s_lo = seg == 0 ? lo : mid;
+    const uint32_t s_hi = seg == 0 ? mid : hi;
+    for (uint32_t b0 = s_lo; b0 < s_hi; b0 += 64) {
+      const uint32_t nb = s_hi - b0 < 64u ? s_hi - b0 : 64u;
+      if ((uint32_t)lane < nb) mine[lane] = ent[b0 + lane];
+      strip_sync();
+      for (uint32_t s = 0; s * G < nb; s += NB) {   // round s + u: lane group g handles entry (s + u) * G + g
+        int32_t xr[NB];
+        float p[NB];
+        bool ok[NB];
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+          const uint32_t idx = (s + u) * G + g;
+          ok[u] = idx < nb;
+          xr[u] = mine[idx % 64].xrow;
+          p[u] = 0.f;
+        }
+        for (int sl = 0; sl < slices; ++sl) {
+          const int c = l * VEC + sl * W;
+          const bool col_ok = c < k;
+          const uint32_t col_bytes = col_ok ? 4u * (uint32_t)c : 0u;
+          const V uu = sl == 0 ? u0 : (col_ok ? vload<VEC>(Urow + c) : vzero<VEC>());
+          V x[NB];
+#pragma unroll
+          for (int u = 0; u < NB; ++u)
+            x[u] = (ok[u] && col_ok) ? load_row<VEC, SMALL>(base, xr[u], row_bytes, col_bytes) : vzero<VEC>();
+#pragma unroll
+          for (int u = 0; u < NB; ++u) p[u] += vdot(uu, x[u]);
+        }
+        const float dot = group_reduce<NB, LPR>(p, l);
+        const uint32_t idx = (s + (uint32_t)(l / SPAN)) * G + g;
+        if (l % SPAN == 0 && idx < nb) S[emap[b0 + idx]] = mine[idx].val * dot;
+      }
+      strip_sync();
+    }
+  }
+}
+
 // One wavefront per split row: its partial vectors (consecutive slots) are
 // summed slot-strided by the G lane groups, then combined by the same butterfly.
 template <int VEC, int LPR>
@@ -527,6 +710,58 @@ int launch_window(const WindowTile* tiles, int64_t n_tiles, int64_t max_span, co
     const size_t lds = (size_t)max_span * LPR * VEC * sizeof(float);
     hipLaunchKernelGGL((window_kernel<VEC, LPR>), grid, dim3(kWinBlock), lds, (hipStream_t)stream, tiles,
                        wrow_ptr, wrow_mid, wrow_y, entries, perm, X, Y, (int)k, accumulate ? 1 : 0);
+    return (int)hipGetLastError();
+  });
+}
+
+namespace {
+template <int LPR> struct BatchOf { static constexpr int value = LPR < 8 ? LPR : 8; };
+}  // namespace
+
+int launch_sddmm_rows(int mode, const uint32_t* item_ptr, const uint32_t* item_mid,
+                      const int32_t* item_row, const uint32_t* item_win, const int32_t* perm,
+                      const Entry* entries, const uint32_t* emap, int64_t n_items, const float* U,
+                      const float* V, int64_t v_rows, const float* Vh, float* S, int32_t k,
+                      void* stream) {
+  if (n_items <= 0) return 0;
+  const Shape s = pick_shape(k, 0);
+  const bool small = small_matrix(v_rows, k);
+  return dispatch_shape(s, [&](auto Vc, auto L) -> int {
+    constexpr int VEC = decltype(Vc)::value, LPR = decltype(L)::value, NB = BatchOf<LPR>::value;
+    const int64_t blocks = ceil_div(ceil_div(n_items, kItemsPerGroupBlock), kDies) * kDies;
+    if (blocks > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
+    dim3 grid((unsigned)blocks);
+#define ARROW_LAUNCH(SM, MD)                                                                       \
+  hipLaunchKernelGGL((sddmm_rows_kernel<VEC, LPR, NB, SM, MD>), grid, dim3(kBlock), 0,             \
+                     (hipStream_t)stream, item_ptr, item_mid, item_row, item_win, perm, entries,   \
+                     emap, n_items, U, V, Vh, S, (int)k, (int)s.slices)
+    if (mode == 0) { if (small) ARROW_LAUNCH(true, 0); else ARROW_LAUNCH(false, 0); }
+    else           { if (small) ARROW_LAUNCH(true, 1); else ARROW_LAUNCH(false, 1); }
+#undef ARROW_LAUNCH
+    return (int)hipGetLastError();
+  });
+}
+
+int launch_sddmm_chunks(const uint32_t* chunk_ptr, const uint32_t* chunk_mid, const int32_t* chunk_row,
+                        const Entry* entries, const uint32_t* emap, int64_t n_chunks, const float* U,
+                        const float* V, int64_t v_rows, const float* Vh, float* S, int32_t k,
+                        void* stream) {
+  if (n_chunks <= 0) return 0;
+  const Shape s = pick_shape(k, 0);
+  const bool small = small_matrix(v_rows, k);
+  return dispatch_shape(s, [&](auto Vc, auto L) -> int {
+    constexpr int VEC = decltype(Vc)::value, LPR = decltype(L)::value, NB = BatchOf<LPR>::value;
+    const int64_t blocks = ceil_div(ceil_div(n_chunks, kBlock / 64), kDies) * kDies;
+    if (blocks > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
+    dim3 grid((unsigned)blocks);
+    if (small)
+      hipLaunchKernelGGL((sddmm_chunks_kernel<VEC, LPR, NB, true>), grid, dim3(kBlock), 0, (hipStream_t)stream,
+                         chunk_ptr, chunk_mid, chunk_row, entries, emap, n_chunks, U, V, Vh, S, (int)k,
+                         (int)s.slices);
+    else
+      hipLaunchKernelGGL((sddmm_chunks_kernel<VEC, LPR, NB, false>), grid, dim3(kBlock), 0, (hipStream_t)stream,
+                         chunk_ptr, chunk_mid, chunk_row, entries, emap, n_chunks, U, V, Vh, S, (int)k,
+                         (int)s.slices);
     return (int)hipGetLastError();
   });
 }

@@ -424,7 +424,7 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
   try {
     img.bytes.assign(total, 0);
     img.entry_src.clear();
-    if (opt.build_entry_map) img.entry_src.assign((size_t)map_total, 0);
+    img.entry_src.assign((size_t)map_total, 0);
   } catch (const std::bad_alloc&) {
     err = "out of host memory while packing the image";
     return ARROW_ENOMEM;
@@ -442,7 +442,7 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
     if (im.n_chunks) std::memcpy(base + im.off_chunk_dst, P.list_dst[1].data(), sizeof(int32_t) * (size_t)im.n_chunks);
     if (im.n_rows) std::memcpy(base + im.off_rows_row, P.list_row[0].data(), sizeof(int32_t) * (size_t)im.n_rows);
     if (im.n_chunks) std::memcpy(base + im.off_chunk_row, P.list_row[1].data(), sizeof(int32_t) * (size_t)im.n_chunks);
-    uint32_t* emap = opt.build_entry_map ? img.entry_src.data() + im.map_offset : nullptr;
+    uint32_t* emap = img.entry_src.data() + im.map_offset;
     std::memcpy(base + im.off_split_ptr, P.split_ptr.data(), sizeof(uint32_t) * P.split_ptr.size());
     if (!P.split_y.empty())
       std::memcpy(base + im.off_split_y, P.split_y.data(), sizeof(int32_t) * P.split_y.size());
@@ -478,7 +478,7 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
       for (uint32_t e = P.list_ptr[0][slot]; e < P.list_ptr[0][slot + 1]; ++e, ++src) {
         ent[e].xrow = L.perm[L.colpos[src]];
         ent[e].val = L.vals[src];
-        if (emap) emap[e] = L.src[src];
+        emap[e] = L.src[src];
       }
     }
     // long rows: items in emission order
@@ -521,7 +521,7 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
               ent[e_out].xrow = L.perm[q];
             }
             ent[e_out].val = L.vals[src0 + e];
-            if (emap) emap[e_out] = L.src[src0 + e];
+            emap[e_out] = L.src[src0 + e];
           }
           list_mid[list][slot] = P.list_ptr[list][slot] + staged_here;
         }
@@ -551,7 +551,7 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
             if (q < b) { ent[e].xrow = L.perm[q]; mid = e + 1; }
             else ent[e].xrow = q - (int32_t)T.win_begin;
             ent[e].val = L.vals[src];
-            if (emap) emap[e] = L.src[src];
+            emap[e] = L.src[src];
           }
           wmid[wr] = mid;
         }
@@ -586,11 +586,25 @@ int verify_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, con
                  std::string& err) {
   if (img.levels.size() != levels.size()) { err = "level count differs"; return ARROW_EINTERNAL; }
   const unsigned char* base = img.bytes.data();
+  // the entry map is a bijection between the image's entries and the caller's nonzeros
+  {
+    int64_t total = 0;
+    for (const HostLevel& L : levels) total += L.rowptr[L.n_i];
+    if ((int64_t)img.entry_src.size() != total) { err = "entry map has the wrong length"; return ARROW_EINTERNAL; }
+    std::vector<uint8_t> hit((size_t)total, 0);
+    for (uint32_t s : img.entry_src) {
+      if ((int64_t)s >= total || hit[s]) { err = "entry map is not a bijection"; return ARROW_EINTERNAL; }
+      hit[s] = 1;
+    }
+  }
   for (size_t li = 0; li < levels.size(); ++li) {
     const HostLevel& L = levels[li];
     const LevelImage& im = img.levels[li];
     const int64_t lev_nnz = L.rowptr[L.n_i];
     const Entry* ent = reinterpret_cast<const Entry*>(base + im.off_entries);
+    const uint32_t* emap = img.entry_src.data() + im.map_offset;
+    std::vector<int32_t> slot_row(im.n_partials, -1);   // vertex named by the item that fills each partial slot
+    std::vector<int32_t> ent_row((size_t)lev_nnz, -1);  // vertex named by the item that holds each entry
     const int32_t* stage_perm = reinterpret_cast<const int32_t*>(base + im.off_stage_perm);
     std::vector<int32_t> produced(n, 0);      // times a Y row is written (directly or by the reduction)
     std::vector<int32_t> slot_writes(im.n_partials, 0);
@@ -603,6 +617,8 @@ int verify_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, con
                                reinterpret_cast<const uint32_t*>(base + im.off_chunk_mid)};
     const int32_t* dsts[2] = {reinterpret_cast<const int32_t*>(base + im.off_rows_dst),
                               reinterpret_cast<const int32_t*>(base + im.off_chunk_dst)};
+    const int32_t* rows_of[2] = {reinterpret_cast<const int32_t*>(base + im.off_rows_row),
+                                 reinterpret_cast<const int32_t*>(base + im.off_chunk_row)};
     const int64_t cnts[2] = {im.n_rows, im.n_chunks};
     uint32_t expect = 0;
     for (int list = 0; list < 2; ++list) {
@@ -611,13 +627,16 @@ int verify_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, con
         if (lo != expect || lo > mid || mid > hi || (int64_t)hi > lev_nnz) { err = "item offsets out of order"; return ARROW_EINTERNAL; }
         expect = hi;
         const int32_t dst = dsts[list][s];
-        if (dst == INT32_MIN) { if (hi != lo) { err = "padding slot with entries"; return ARROW_EINTERNAL; } continue; }
+        const int32_t row = rows_of[list][s];
+        if (dst == INT32_MIN) { if (hi != lo || row != -1) { err = "padding slot with entries"; return ARROW_EINTERNAL; } continue; }
+        if (row < 0 || row >= n || (dst >= 0 && dst != row)) { err = "item vertex differs from its Y row"; return ARROW_EINTERNAL; }
         double sum = 0.0;
         for (uint32_t e = lo; e < hi; ++e) {
           int64_t xr = ent[e].xrow;
           if (e < mid) { if (xr < 0 || xr >= im.n_stage) { err = "staged row out of range"; return ARROW_EINTERNAL; } xr = stage_perm[xr]; }
           if (xr < 0 || xr >= n) { err = "X row out of range"; return ARROW_EINTERNAL; }
           sum += (double)ent[e].val * (double)(1 + xr);
+          ent_row[e] = row;
         }
         covered += hi - lo;
         if (dst >= 0) {
@@ -626,7 +645,7 @@ int verify_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, con
         } else {
           const int64_t slot = -1 - (int64_t)dst;
           if (slot >= im.n_partials) { err = "partial slot out of range"; return ARROW_EINTERNAL; }
-          ++slot_writes[slot]; slot_sum[slot] += sum;
+          ++slot_writes[slot]; slot_sum[slot] += sum; slot_row[slot] = row;
         }
       }
     }
@@ -637,7 +656,10 @@ int verify_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, con
     for (int64_t r = 0; r < im.n_split; ++r) {
       if (sp[r] >= sp[r + 1] || sy[r] < 0 || sy[r] >= n) { err = "bad split row"; return ARROW_EINTERNAL; }
       ++produced[sy[r]];
-      for (uint32_t sl = sp[r]; sl < sp[r + 1]; ++sl) checksum[sy[r]] += slot_sum[sl];
+      for (uint32_t sl = sp[r]; sl < sp[r + 1]; ++sl) {
+        checksum[sy[r]] += slot_sum[sl];
+        if (slot_row[sl] != sy[r]) { err = "a partial's item names another vertex than its split row"; return ARROW_EINTERNAL; }
+      }
     }
     for (int64_t sl = 0; sl < im.n_partials; ++sl)
       if (slot_writes[sl] != 1) { err = "a partial slot is not written exactly once"; return ARROW_EINTERNAL; }
@@ -646,6 +668,7 @@ int verify_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, con
     const uint32_t* wp = reinterpret_cast<const uint32_t*>(base + im.off_wrow_ptr);
     const uint32_t* wm = reinterpret_cast<const uint32_t*>(base + im.off_wrow_mid);
     const int32_t* wy = reinterpret_cast<const int32_t*>(base + im.off_wrow_y);
+    const uint32_t* ww = reinterpret_cast<const uint32_t*>(base + im.off_wrow_win);
     uint32_t wexpect = 0;
     for (int64_t t = 0; t < im.n_wtiles; ++t) {
       if (wt[t].row_begin != wexpect || wt[t].row_end <= wt[t].row_begin || (int64_t)wt[t].row_end > im.n_wrows ||
@@ -658,6 +681,7 @@ int verify_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, con
         if (lo != expect || lo > mid || mid > hi || (int64_t)hi > lev_nnz) { err = "window row offsets out of order"; return ARROW_EINTERNAL; }
         expect = hi;
         if (wy[wr] < 0 || wy[wr] >= n) { err = "window Y row out of range"; return ARROW_EINTERNAL; }
+        if (ww[wr] != wt[t].win_begin) { err = "window row names another window than its tile"; return ARROW_EINTERNAL; }
         ++produced[wy[wr]];
         double sum = 0.0;
         for (uint32_t e = lo; e < hi; ++e) {
@@ -668,12 +692,30 @@ int verify_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, con
           }
           if (xr < 0 || xr >= n) { err = "X row out of range"; return ARROW_EINTERNAL; }
           sum += (double)ent[e].val * (double)(1 + xr);
+          ent_row[e] = wy[wr];
         }
         checksum[wy[wr]] += sum;
         covered += hi - lo;
       }
     }
     if (wexpect != (uint32_t)im.n_wrows) { err = "window rows not covered by tiles"; return ARROW_EINTERNAL; }
+    {
+      // the map sends every image entry to a nonzero of this level with the same value and row
+      std::vector<uint32_t> order((size_t)lev_nnz);
+      std::vector<int32_t> lev_row((size_t)lev_nnz);
+      for (int64_t p = 0; p < L.n_i; ++p)
+        for (int64_t e = L.rowptr[p]; e < L.rowptr[p + 1]; ++e) lev_row[e] = L.perm[p];
+      for (int64_t e = 0; e < lev_nnz; ++e) order[e] = (uint32_t)e;
+      std::sort(order.begin(), order.end(), [&](uint32_t x, uint32_t y) { return L.src[x] < L.src[y]; });
+      for (int64_t e = 0; e < lev_nnz; ++e) {
+        auto it = std::lower_bound(order.begin(), order.end(), emap[e],
+                                   [&](uint32_t x, uint32_t key) { return L.src[x] < key; });
+        if (it == order.end() || L.src[*it] != emap[e] || lev_row[*it] != ent_row[e] ||
+            std::memcmp(&L.vals[*it], &ent[e].val, sizeof(float)) != 0) {
+          err = "entry map points at a nonzero with another value or row"; return ARROW_EINTERNAL;
+        }
+      }
+    }
     if (covered != lev_nnz) { err = "entries not covered exactly once"; return ARROW_EINTERNAL; }
     // every row of the level produced exactly once, with the right entries
     for (int64_t p = 0; p < L.n_i; ++p) {

@@ -264,6 +264,26 @@ def test_save_and_load_round_trip(tmp_path, monkeypatch):
     bad.write_bytes(bytes(blob))
     with pytest.raises(binding.ArrowError):
         binding.arrow_load(str(bad))
+    # two entries that claim the same nonzero of the caller's CSR
+    src_off = col_off + 8 * lev_nnz
+    src = np.frombuffer(raw, np.uint32, lev_nnz, src_off).copy()
+    assert len(np.unique(src)) == lev_nnz and src.max() < w.nnz
+    # the stored source indices name the right nonzeros: same value, same row and column vertex
+    perm0 = np.frombuffer(raw, np.int32, n_i, levels_off + 8 + 8 + 32 + 4)
+    rp0 = np.frombuffer(raw, np.int64, n_i + 1, levels_off + 8 + 8 + 32 + 4 + 4 * n_i)
+    vals0 = np.frombuffer(raw, np.float32, lev_nnz, col_off + 4 * lev_nnz)
+    cols0 = np.frombuffer(raw, np.int32, lev_nnz, col_off)
+    assert np.array_equal(w.vals[src].view(np.uint32), vals0.view(np.uint32))
+    assert np.array_equal(w.colidx[src], perm0[cols0])
+    csr_row = np.repeat(np.arange(w.n), np.diff(w.rowptr))
+    assert np.array_equal(csr_row[src], perm0[np.repeat(np.arange(n_i), np.diff(rp0))])
+    src[0] = src[1]
+    blob = bytearray(raw)
+    blob[src_off:src_off + 4 * lev_nnz] = src.tobytes()
+    bad.write_bytes(bytes(blob))
+    with pytest.raises(binding.ArrowError) as ei:
+        binding.arrow_load(str(bad))
+    assert "bijection" in str(ei.value)
     with pytest.raises(binding.ArrowError):
         binding.arrow_load(str(tmp_path / "does_not_exist"))
 
