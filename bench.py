@@ -6,6 +6,9 @@ One "step" is one whole product Y = A.X = sum_i P_i^T B_i (P_i X) through
 with inputs already resident in HBM.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--shrink S]
+
+``--op sddmm`` times the sampled dense-dense product S = A .* (U V^T) over the same arrow
+layout instead (one step = one ``arrow_sddmm`` call); the default, and the headline, is the product.
 """
 from __future__ import annotations
 
@@ -21,6 +24,23 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0      # MI355X published HBM3E peak
+
+
+def algorithmic_bytes_sddmm(levels, n, k):
+    """Bytes one sampled product must move, per launch and for the whole path: per stored entry
+    8 B (row id + value) + 4 B (entry map) read and 4 B of S written; the work-list words; every
+    distinct V row a launch references and the U row of every row it handles, read once."""
+    row = 4 * k
+    per = {}
+    for i, L in enumerate(levels):
+        per[("rows", i)] = 16 * L["nnz_rows"] + 12 * L["short_rows"] + 4 + row * (L["x_rows_rows"] + L["short_rows"] - L["rows_partials"])
+        per[("chunks", i)] = 16 * L["nnz_chunks"] + 12 * L["chunks"] + 4 + row * (L["x_rows_chunks"] + L["chunks"] - L["chunks_partials"] + L["split_rows"])
+        per[("window", i)] = 16 * L["nnz_window"] + 16 * L["window_rows"] + row * 2 * L["window_rows"]
+        per[("panel", i)] = 16 * L["nnz_panel"] + 4 * L["panel_bins"] + row * 2 * L["panel_rows"]
+        per[("reduce", i)] = 0
+        per[("stage", i)] = 0
+    path = 16 * sum(L["nnz"] for L in levels) + 2 * row * n
+    return per, path
 
 
 def algorithmic_bytes(levels, n, k):
@@ -42,6 +62,9 @@ def algorithmic_bytes(levels, n, k):
         per[("reduce", i)] = 8 * L["split_rows"] + 4 + row * (L["partials"] + rmw * L["split_rows"])
         per[("window", i)] = 8 * L["nnz_window"] + 12 * L["window_rows"] + row * (1 + rmw) * L["window_rows"]
         per[("stage", i)] = 0
+        # panels: entries, every staged head row once, the eight class results written and read,
+        # Y read and written
+        per[("panel", i)] = 8 * L["nnz_panel"] + 4 * L["panel_bins"] + row * (18 * L["panel_rows"]) if L["panel_rows"] else 0
     # whole product: X is read at least once and Y written once, whatever the kernel split
     path = sum(8 * L["nnz"] + 12 * (L["short_rows"] + L["chunks"] + L["window_rows"]) for L in levels) + 2 * row * n
     path += sum(row * 3 * (L["short_rows"] + L["chunks"] - L["partials"] + L["split_rows"] + L["window_rows"])
@@ -63,6 +86,8 @@ def main() -> int:
                          "n*k*4 written each) so that counter runs can be scaled")
     ap.add_argument("--no-profile-pass", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--kc", type=int, default=None)
+    ap.add_argument("--op", choices=("spmm", "sddmm"), default="spmm",
+                    help="spmm: Y = A.X (the headline); sddmm: S = A .* (U V^T) on the same layout")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -90,11 +115,23 @@ def main() -> int:
     Y = torch.empty_like(X)
     k, n, nnz = w.k, w.n, w.nnz
     levels = op.levels()
-    l = w.l
+    sampled = args.op == "sddmm"
+    l = 1 if sampled else w.l
+    if sampled:
+        # U = the workload's X, V = a second seeded normal matrix of the same shape
+        Vh = synth.normal_matrix(n, k, seed=w.seed_x + 1)
+        V = torch.from_numpy(Vh).to(dev)
+        S = torch.empty(nnz, dtype=torch.float32, device=dev)
+
+    def run_once():
+        if sampled:
+            op.sddmm(X, V, S)
+        else:
+            op.spmm(X, Y)
 
     def step():
-        if l == 1:
-            op.spmm(X, Y)
+        if sampled or l == 1:
+            run_once()
         else:
             Y.copy_(X)
             op.spmm_iter(Y, l)
@@ -120,18 +157,18 @@ def main() -> int:
     acc = {}
     lev_acc = {}
     for _ in range(prof_runs):
-        op.spmm(X, Y)
+        run_once()
         p = binding.arrow_get_profile(op.h)
         for key, v in p.items():
             acc[key] = acc.get(key, 0) + v
         for i in range(len(levels)):
             pl = binding.arrow_get_level_profile(op.h, i)
-            for cls in ("rows", "chunks", "reduce", "stage", "window"):
+            for cls in ("rows", "chunks", "reduce", "stage", "window", "panel"):
                 lev_acc[(cls, i)] = lev_acc.get((cls, i), 0.0) + pl[cls + "_ms"]
     binding.arrow_set_profiling(op.h, False)
     prof = {key: v / prof_runs for key, v in acc.items()}
     launch_ms = {key: v / prof_runs for key, v in lev_acc.items()}
-    per_bytes, path_bytes = algorithmic_bytes(levels, n, k)
+    per_bytes, path_bytes = (algorithmic_bytes_sddmm if sampled else algorithmic_bytes)(levels, n, k)
     # the dominant kernel = the single launch (kernel class, level) that takes the most time;
     # at the headline workload that is the chunk kernel of level 0
     dom = max(launch_ms, key=launch_ms.get)
@@ -139,11 +176,12 @@ def main() -> int:
     bytes_per_launch = per_bytes[dom]
     achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{dom[0]}_kernel_level{dom[1]}_{w.name}.json")
+    kname = ("sddmm_" if sampled else "") + dom[0]
+    tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{kname}_kernel_level{dom[1]}_{w.name}.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
             traffic = json.load(f).get("hbm_bytes_per_launch")
-    roofline = {"bound": "hbm", "kernel": f"{dom[0]}_kernel (level {dom[1]})", "achieved": round(achieved, 1),
+    roofline = {"bound": "hbm", "kernel": f"{kname}_kernel (level {dom[1]})", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": traffic, "avg_launch_ms": round(avg_ms, 4), "launches_per_step": 1,
                 "algorithmic_bytes_per_launch": int(bytes_per_launch)}
@@ -151,7 +189,41 @@ def main() -> int:
     # ---- quick correctness sanity + CPU baseline: the oracle on a bounded row sample ----------
     cpu_baseline = None
     check = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and sampled:
+        import oracle
+        op.sddmm(X, V, S)
+        torch.cuda.synchronize()
+
+        def sample_rows(stride):            # the operand with only every stride-th row kept
+            rows = np.arange(0, n, stride, dtype=np.int64)
+            cnt = np.zeros(n, np.int64)
+            cnt[rows] = w.rowptr[rows + 1] - w.rowptr[rows]
+            rp = np.concatenate([[0], np.cumsum(cnt)])
+            lens = cnt[rows]
+            first = np.cumsum(lens) - lens                       # where each kept row starts in the sample
+            idx = np.repeat(w.rowptr[rows] - first, lens) + np.arange(int(lens.sum()), dtype=np.int64)
+            return rows, rp, idx
+
+        rows, rp, idx = sample_rows(max(1, n // 4096))
+        t0 = time.perf_counter()
+        oracle.sddmm(rp, w.colidx[idx], w.vals[idx], Xh, Vh)
+        t_cal = time.perf_counter() - t0
+        rate = max(len(idx), 1) / max(t_cal, 1e-6)
+        want = min(nnz, int(rate * args.cpu_seconds))
+        stride = max(1, int(round(nnz / max(want, 1))))
+        rows, rp, idx = sample_rows(stride)
+        t0 = time.perf_counter()
+        Sref, B = oracle.sddmm(rp, w.colidx[idx], w.vals[idx], Xh, Vh)
+        t_cpu = time.perf_counter() - t0
+        cpu_baseline = {"value": round(2.0 * len(idx) * k / t_cpu / 1e9, 3), "unit": "GFLOP/s",
+                        "cores": oracle.num_threads(), "kind": "oracle",
+                        "sample": f"every {stride}th row of the same operand, all k={k} columns: "
+                                  f"{len(rows)} rows, {len(idx)} nonzeros, {t_cpu:.1f} s"}
+        Ss = S[torch.from_numpy(idx).to(dev)].cpu().numpy().astype(np.float64)
+        ratio = np.abs(Ss - Sref) / np.maximum(B, 1e-300)
+        check = {"entries": int(len(idx)), "max_err_over_bound": float(ratio.max()), "tolerance": 1e-5,
+                 "ok": bool(ratio.max() <= 1e-5)}
+    elif not args.no_cpu_baseline:
         import oracle
         op.spmm(X, Y)
         torch.cuda.synchronize()
@@ -179,12 +251,13 @@ def main() -> int:
                  "ok": bool(ratio.max() <= 1e-5)}
 
     out = {
-        "metric": "fp32 A.X GFLOP/s (2*nnz*k), arrow-decomposed SpMM",
+        "metric": ("fp32 A .* (U V^T) GFLOP/s (2*nnz*k), sampled dense-dense product on the arrow layout" if sampled
+                   else "fp32 A.X GFLOP/s (2*nnz*k), arrow-decomposed SpMM"),
         "value": round(gflops, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "n": n, "nnz": nnz, "k": k, "b": w.b, "products": l,
-                   "levels": op.info["levels"], "tuning": {"kc": args.kc}},
+                   "levels": op.info["levels"], "op": args.op, "tuning": {"kc": args.kc}},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "whole_path": {"algorithmic_GB": round(path_bytes / 1e9, 3),

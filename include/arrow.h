@@ -90,6 +90,9 @@ typedef struct arrow_level_info_t {
   int64_t nnz_window;   /* entries of those rows                                 */
   int64_t rows_partials;  /* lane-group items that write a partial vector        */
   int64_t chunks_partials;/* wavefront items that write a partial vector         */
+  int64_t panel_rows;   /* head rows whose head-block entries run in panels (accumulators in LDS) */
+  int64_t panel_bins;   /* lane-group entry streams of those panels              */
+  int64_t nnz_panel;    /* entries held by the panels                            */
   int32_t blocks;       /* ceil(n_i / b)                                         */
   int32_t separator_rule; /* 1 if block separators were promoted into the head   */
 } arrow_level_info_t;
@@ -103,6 +106,8 @@ typedef struct arrow_profile_t {
   float window_ms;  /* diagonal-block tiles with the X window staged in LDS                               */
   float total_ms;   /* first launch to last launch of the product                                         */
   int32_t rows_launches, chunks_launches, reduce_launches, stage_launches, window_launches; /* launches per class (one per level that has such work) */
+  float panel_ms;   /* head panels: head-block entries of sparse head rows, accumulators in LDS          */
+  int32_t panel_launches;
 } arrow_profile_t;
 
 /*
@@ -192,6 +197,9 @@ int arrow_self_check(const arrow_handle *h);
  *               head is staged and k > 64, the whole row (up to 256 columns) otherwise
  *   "l2_resident_bytes"  share of one die's 4 MiB L2 that a resident slice of the staged head
  *               may take when kc is chosen automatically (default 2 MiB)
+ *   "sddmm_image_order"  1: arrow_sddmm writes S in the order of the packed image instead of the
+ *               caller's CSR order (contiguous stores; arrow_export_entry_map tells which nonzero
+ *               each element belongs to); default 0
  * Pack-time choices are read from the environment by arrow_decompose: ARROW_SHORT_MAX (rows
  * with at most this many entries are handled one per lane group, default 16), ARROW_CHUNK_NNZ
  * (most entries per wavefront chunk, default 256), ARROW_WINDOW_ROWS (long rows are cut at
@@ -208,8 +216,13 @@ int arrow_self_check(const arrow_handle *h);
  * kept when its diagonal-block entries number at least this / 10 times its span, default 80),
  * ARROW_WINDOW_SHARE_X1000 (the tiles of a level are kept when they hold at least this / 1000 of
  * the level's entries, default 50),
+ * ARROW_PANEL (1: head rows of level 0 with few entries per column window run their head-block
+ * entries in panels: 256 rows per group, one workgroup per group and column class with the
+ * group's accumulators in LDS, class c served by accelerator die c; default 0), ARROW_PANEL_MIN
+ * (fewest head-block entries of a row that joins a panel, default 8),
  * ARROW_SEPARATORS and ARROW_BFS_TAIL (0 disables the separator rule / the breadth-first
- * arrangement of later levels).
+ * arrangement of later levels), ARROW_HEAD_BY_ID (1, the default: the head vertices of the plain
+ * rule sit in id order inside the head; 0: by falling degree).
  * Errors: EINVAL (unknown name, value out of range).
  */
 int arrow_set_option(arrow_handle *h, const char *name, int64_t value);
@@ -243,12 +256,15 @@ int arrow_get_level_profile(arrow_handle *h, int32_t level, arrow_profile_t *out
  * written exactly once, nothing is accumulated).  Needs arrow_upload, arrow_sddmm_upload and a
  * workspace of arrow_workspace_bytes(h, k).  Launches on `stream` and returns without waiting.
  * fp32 arithmetic, deterministic summation order.
+ * arrow_export_entry_map copies the entry map to `out` (HOST, nnz uint32): element e of an
+ * image-order S (option "sddmm_image_order") is the nonzero out[e] of the caller's CSR arrays.
  * Errors: EINVAL (NULL, alignment, k < 1), ENOTREADY (no image / map / workspace), ETOOSMALL
  * (buffer or workspace too small), EHIP.
  */
 size_t arrow_sddmm_device_bytes(const arrow_handle *h);
 int arrow_sddmm_upload(arrow_handle *h, void *dev_buf, size_t bytes, void *stream);
 int arrow_sddmm(arrow_handle *h, const float *U, const float *V, float *S, int32_t k, void *stream);
+int arrow_export_entry_map(const arrow_handle *h, uint32_t *out);
 
 /*
  * Persistence (host only).  arrow_save writes the arrow matrices of a handle (permutations and

@@ -23,7 +23,7 @@ ARROW_OK, ARROW_EINVAL, ARROW_ENOMEM, ARROW_ENOTREADY, ARROW_ETOOSMALL, ARROW_EH
 EXPORTED = [
     "arrow_decompose", "arrow_device_bytes", "arrow_upload", "arrow_workspace_bytes",
     "arrow_set_workspace", "arrow_spmm", "arrow_spmm_iter", "arrow_sddmm_device_bytes",
-    "arrow_sddmm_upload", "arrow_sddmm", "arrow_gather", "arrow_info",
+    "arrow_sddmm_upload", "arrow_sddmm", "arrow_export_entry_map", "arrow_gather", "arrow_info",
     "arrow_level_info", "arrow_export_level", "arrow_self_check", "arrow_set_option", "arrow_set_profiling",
     "arrow_get_profile", "arrow_get_level_profile", "arrow_save", "arrow_load", "arrow_last_error",
     "arrow_destroy",
@@ -47,7 +47,7 @@ class arrow_level_info_t(ctypes.Structure):
                 ("n_i", "nnz", "nnz_head_head", "nnz_head_row", "nnz_head_col", "nnz_diag",
                  "short_rows", "chunks", "split_rows", "partials", "nnz_rows", "nnz_chunks",
                  "x_rows_rows", "x_rows_chunks", "window_tiles", "window_rows", "nnz_window",
-                 "rows_partials", "chunks_partials")] + \
+                 "rows_partials", "chunks_partials", "panel_rows", "panel_bins", "nnz_panel")] + \
                [("blocks", ctypes.c_int32), ("separator_rule", ctypes.c_int32)]
 
 
@@ -56,7 +56,8 @@ class arrow_profile_t(ctypes.Structure):
                 ("rows_ms", "chunks_ms", "reduce_ms", "stage_ms", "window_ms", "total_ms")] + \
                [(name, ctypes.c_int32) for name in
                 ("rows_launches", "chunks_launches", "reduce_launches", "stage_launches",
-                 "window_launches")]
+                 "window_launches")] + \
+               [("panel_ms", ctypes.c_float), ("panel_launches", ctypes.c_int32)]
 
 
 def lib():
@@ -89,6 +90,8 @@ def lib():
     L.arrow_sddmm_upload.argtypes = [vp, vp, sz, vp]
     L.arrow_sddmm.restype = ctypes.c_int
     L.arrow_sddmm.argtypes = [vp, vp, vp, vp, i32, vp]
+    L.arrow_export_entry_map.restype = ctypes.c_int
+    L.arrow_export_entry_map.argtypes = [vp, vp]
     L.arrow_gather.restype = ctypes.c_int
     L.arrow_gather.argtypes = [vp, i32, vp, vp, i32, vp]
     L.arrow_info.restype = ctypes.c_int
@@ -175,6 +178,13 @@ def arrow_sddmm_upload(h: int, dev_ptr: int, nbytes: int, stream: int = 0) -> No
 
 def arrow_sddmm(h: int, u_ptr: int, v_ptr: int, s_ptr: int, k: int, stream: int = 0) -> None:
     _check(lib().arrow_sddmm(h, u_ptr, v_ptr, s_ptr, k, stream))
+
+
+def arrow_export_entry_map(h: int) -> np.ndarray:
+    """Host copy of the entry map: image order -> index in the caller's CSR arrays."""
+    out = np.empty(arrow_info(h)["nnz"], dtype=np.uint32)
+    _check(lib().arrow_export_entry_map(h, out.ctypes.data))
+    return out
 
 
 def arrow_gather(h: int, level: int, x_ptr: int, xp_ptr: int, k: int, stream: int = 0) -> None:

@@ -42,7 +42,7 @@ int64_t env_int(const char* name, int64_t dflt) {
 constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
-enum KernelClass { kRows = 0, kChunks = 1, kReduce = 2, kStage = 3, kWindow = 4, kClasses = 5 };
+enum KernelClass { kRows = 0, kChunks = 1, kReduce = 2, kStage = 3, kWindow = 4, kPanel = 5, kClasses = 6 };
 
 struct Span {
   int cls;
@@ -65,6 +65,7 @@ struct arrow_handle {
   unsigned char* ws = nullptr;
   size_t ws_bytes = 0;
   const uint32_t* dev_map = nullptr;   // entry map (sampled product only)
+  bool sddmm_image_order = false;
   // profiling
   bool profiling = false;
   std::vector<Span> spans;   // event pool, reused between products
@@ -73,12 +74,16 @@ struct arrow_handle {
 
 namespace {
 
-// workspace layout: [partial vectors][staged head rows][n x k buffer of the chained products]
+// workspace layout: [partial vectors][staged head rows][panel class results][n x k buffer of the chained products]
 size_t partial_bytes(const arrow_handle* h, int32_t k) {
   return align_up((size_t)h->img.max_partials * (size_t)k * sizeof(float));
 }
 size_t stage_bytes(const arrow_handle* h, int32_t k) {
   return align_up((size_t)h->img.max_stage_rows * (size_t)k * sizeof(float));
+}
+
+size_t panel_bytes(const arrow_handle* h, int32_t k) {
+  return align_up((size_t)h->img.max_panel_slots * arrow::kDies * (size_t)k * sizeof(float));
 }
 
 template <typename T>
@@ -117,6 +122,7 @@ int check_hip(int rc, const char* what) {
 int product(arrow_handle* h, const float* X, float* Y, int32_t k, hipStream_t stream) {
   float* partials = reinterpret_cast<float*>(h->ws);
   float* stage = reinterpret_cast<float*>(h->ws + partial_bytes(h, k));
+  float* panel_part = reinterpret_cast<float*>(h->ws + partial_bytes(h, k) + stage_bytes(h, k));
   for (size_t li = 0; li < h->img.levels.size(); ++li) {
     const arrow::LevelImage& im = h->img.levels[li];
     const bool acc = li > 0;
@@ -177,18 +183,29 @@ int product(arrow_handle* h, const float* X, float* Y, int32_t k, hipStream_t st
                                     im.n_split, partials, Y, k, acc, stream);
       if (rc) return check_hip(rc, "reduce kernel launch");
     }
+    if (im.n_panel_groups > 0) {
+      // last: the panels add to rows of Y the launches above have stored
+      Scoped sc(h, kPanel, (int)li, stream);
+      int rc = arrow::launch_panel(at<uint32_t>(h, im.off_panel_ptr), at<int32_t>(h, im.off_panel_y), ent,
+                                   im.n_panel_groups, Xh, im.n_stage, panel_part, k, stream);
+      if (rc) return check_hip(rc, "panel kernel launch");
+      rc = arrow::launch_panel_combine(at<int32_t>(h, im.off_panel_y), im.n_panel_groups * arrow::kPanelRows,
+                                       panel_part, Y, k, stream);
+      if (rc) return check_hip(rc, "panel combine launch");
+    }
   }
   return ARROW_OK;
 }
 
 // S = A .* (U V^T) on the pattern of A, level by level; every stored entry is written once
-int sampled_product(arrow_handle* h, const float* U, const float* V, float* S, int32_t k,
+int sampled_product(arrow_handle* h, const float* U, const float* V, float* S_out, int32_t k,
                     hipStream_t stream) {
   float* stage = reinterpret_cast<float*>(h->ws + partial_bytes(h, k));
   for (size_t li = 0; li < h->img.levels.size(); ++li) {
     const arrow::LevelImage& im = h->img.levels[li];
     const arrow::Entry* ent = at<arrow::Entry>(h, im.off_entries);
-    const uint32_t* emap = h->dev_map + im.map_offset;
+    const uint32_t* emap = h->sddmm_image_order ? nullptr : h->dev_map + im.map_offset;
+    float* S = h->sddmm_image_order ? S_out + im.map_offset : S_out;
     const float* Vh = V;
     if (im.staged) {
       Scoped sc(h, kStage, (int)li, stream);
@@ -218,6 +235,12 @@ int sampled_product(arrow_handle* h, const float* U, const float* V, float* S, i
                                         V, S, k, stream);
       if (rc) return check_hip(rc, "sampled window-rows kernel launch");
     }
+    if (im.n_panel_bins > 0) {
+      Scoped sc(h, kPanel, (int)li, stream);
+      int rc = arrow::launch_sddmm_panel(at<uint32_t>(h, im.off_panel_ptr), at<int32_t>(h, im.off_panel_y),
+                                         ent, emap, im.n_panel_bins, U, Vh, im.n_stage, S, k, stream);
+      if (rc) return check_hip(rc, "sampled panel kernel launch");
+    }
   }
   return ARROW_OK;
 }
@@ -233,6 +256,8 @@ void read_pack_options(arrow_handle* h) {
   h->pack.class_min = (int32_t)env_int("ARROW_CLASS_MIN", h->pack.class_min);
   h->pack.piece_max = (int32_t)env_int("ARROW_PIECE_MAX", h->pack.piece_max);
   h->pack.stage_head = (int32_t)env_int("ARROW_STAGE_HEAD", h->pack.stage_head);
+  h->pack.panel = (int32_t)env_int("ARROW_PANEL", h->pack.panel);
+  h->pack.panel_min = (int32_t)env_int("ARROW_PANEL_MIN", h->pack.panel_min);
   h->pack.window_span = (int32_t)env_int("ARROW_WINDOW_SPAN", h->pack.window_span);
   if (h->pack.window_span > 4096) h->pack.window_span = 4096;   // 4096 positions x 4 columns x 4 B = 64 KiB of LDS
   h->pack.window_tile_rows = (int32_t)env_int("ARROW_WINDOW_TILE_ROWS", h->pack.window_tile_rows);
@@ -247,7 +272,7 @@ int ready(const arrow_handle* h, int32_t k, bool need_iter_buffer) {
   if (k < 1) return fail(ARROW_EINVAL, "k must be >= 1 (got %d)", k);
   if (!h->dev) return fail(ARROW_ENOTREADY, "arrow_upload has not been called");
   if (!h->ws) return fail(ARROW_ENOTREADY, "arrow_set_workspace has not been called");
-  size_t need = partial_bytes(h, k) + stage_bytes(h, k);
+  size_t need = partial_bytes(h, k) + stage_bytes(h, k) + panel_bytes(h, k);
   if (need_iter_buffer) need += (size_t)h->n * (size_t)k * sizeof(float);
   if (h->ws_bytes < need)
     return fail(ARROW_ETOOSMALL, "workspace holds %zu bytes, k = %d needs %zu", h->ws_bytes, k, need);
@@ -345,6 +370,7 @@ int arrow_decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, con
   arrow::DecomposeOptions dopt;
   dopt.separators = env_int("ARROW_SEPARATORS", 1) != 0;
   dopt.bfs_tail = env_int("ARROW_BFS_TAIL", 1) != 0;
+  dopt.head_by_id = env_int("ARROW_HEAD_BY_ID", 1) != 0;
   read_pack_options(h);
   std::string err;
   int rc;
@@ -384,7 +410,8 @@ int arrow_upload(arrow_handle* h, void* dev_buf, size_t bytes, void* stream) {
 
 size_t arrow_workspace_bytes(const arrow_handle* h, int32_t k) {
   if (!h || k < 1) return 0;
-  return partial_bytes(h, k) + stage_bytes(h, k) + align_up((size_t)h->n * (size_t)k * sizeof(float));
+  return partial_bytes(h, k) + stage_bytes(h, k) + panel_bytes(h, k) +
+         align_up((size_t)h->n * (size_t)k * sizeof(float));
 }
 
 int arrow_set_workspace(arrow_handle* h, void* dev_ws, size_t bytes) {
@@ -414,7 +441,7 @@ int arrow_spmm_iter(arrow_handle* h, float* X, int32_t k, int32_t l, void* strea
   if ((uintptr_t)X % 16) return fail(ARROW_EINVAL, "X must be 16-byte aligned");
   if (l == 0) return ARROW_OK;
   h->spans_used = 0;
-  float* tmp = reinterpret_cast<float*>(h->ws + partial_bytes(h, k) + stage_bytes(h, k));
+  float* tmp = reinterpret_cast<float*>(h->ws + partial_bytes(h, k) + stage_bytes(h, k) + panel_bytes(h, k));
   float* src = X;
   float* dst = tmp;
   for (int32_t t = 0; t < l; ++t) {
@@ -460,6 +487,13 @@ int arrow_sddmm(arrow_handle* h, const float* U, const float* V, float* S, int32
   return sampled_product(h, U, V, S, k, (hipStream_t)stream);
 }
 
+int arrow_export_entry_map(const arrow_handle* h, uint32_t* out) {
+  if (!h || (!out && !h->img.entry_src.empty())) return fail(ARROW_EINVAL, "NULL argument");
+  if (!h->img.entry_src.empty())
+    std::memcpy(out, h->img.entry_src.data(), sizeof(uint32_t) * h->img.entry_src.size());
+  return ARROW_OK;
+}
+
 int arrow_gather(arrow_handle* h, int32_t level, const float* X, float* Xp, int32_t k, void* stream) {
   if (!h) return fail(ARROW_EINVAL, "handle is NULL");
   if (level < 0 || (size_t)level >= h->img.levels.size()) return fail(ARROW_EINVAL, "no level %d", level);
@@ -494,6 +528,7 @@ int arrow_level_info(const arrow_handle* h, int32_t level, arrow_level_info_t* o
   out->partials = im.n_partials; out->nnz_rows = im.nnz_rows; out->nnz_chunks = im.nnz_chunks;
   out->x_rows_rows = im.x_rows_rows; out->x_rows_chunks = im.x_rows_chunks;
   out->window_tiles = im.n_wtiles; out->window_rows = im.n_wrows; out->nnz_window = im.nnz_w;
+  out->panel_rows = im.n_panel_rows; out->panel_bins = im.n_panel_bins; out->nnz_panel = im.nnz_panel;
   out->blocks = (int32_t)((L.n_i + h->b - 1) / h->b);
   out->separator_rule = L.separator_rule ? 1 : 0;
   return ARROW_OK;
@@ -529,6 +564,8 @@ int arrow_set_option(arrow_handle* h, const char* name, int64_t value) {
   if (!std::strcmp(name, "kc")) {
     if (value < 0 || value > 256) return fail(ARROW_EINVAL, "kc must be in [0, 256]");
     h->tuning.kc = (int32_t)value;
+  } else if (!std::strcmp(name, "sddmm_image_order")) {
+    h->sddmm_image_order = value != 0;
   } else if (!std::strcmp(name, "l2_resident_bytes")) {
     if (value < 0) return fail(ARROW_EINVAL, "l2_resident_bytes must be >= 0");
     h->tuning.l2_resident_bytes = value;
@@ -555,9 +592,9 @@ int arrow_get_level_profile(arrow_handle* h, int32_t level, arrow_profile_t* out
   hipError_t e = hipEventSynchronize(h->spans[h->spans_used - 1].b);
   if (e != hipSuccess) return check_hip((int)e, "event synchronize");
   float* slot[kClasses] = {&out->rows_ms, &out->chunks_ms, &out->reduce_ms, &out->stage_ms,
-                           &out->window_ms};
+                           &out->window_ms, &out->panel_ms};
   int32_t* count[kClasses] = {&out->rows_launches, &out->chunks_launches, &out->reduce_launches,
-                              &out->stage_launches, &out->window_launches};
+                              &out->stage_launches, &out->window_launches, &out->panel_launches};
   for (size_t i = 0; i < h->spans_used; ++i) {
     if (level >= 0 && h->spans[i].level != level) continue;
     float ms = 0.f;

@@ -25,6 +25,7 @@ struct DecomposeOptions {
   double hub_factor = 8.0;   // a vertex is a hub when its degree exceeds hub_factor * mean degree
   bool separators = true;    // try the block-separator rule before the plain top-degree head
   bool bfs_tail = true;      // levels >= 1 arrange the non-head vertices in BFS order
+  bool head_by_id = true;    // plain rule: head vertices in id order (else by falling degree)
 };
 
 // Peels arrow matrices of width b off A until nothing is left.  Returns 0 or a
@@ -46,6 +47,14 @@ struct Entry {
 constexpr int kDies = 8;             // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
 constexpr int kChunksPerGroup = 4;   // wave-list items (one per wavefront) per workgroup of the chunk kernel
 constexpr int kItemsPerGroupBlock = 64;  // group-list items per workgroup of the rows kernel, whatever its lane-group width
+// head panels: kPanelRows head rows form a group; the group's head-block entries are dealt by column
+// class (staged head row mod kDies) to kDies workgroups, one per accelerator die, each keeping the
+// group's accumulators in LDS and streaming its entries in kPanelBins lane-group streams
+constexpr int kPanelBins = 32;
+constexpr int kPanelRows = 256;
+constexpr int kPanelClassShift = 6;       // staged head rows are dealt to the column classes 64 at a time
+inline int panel_class(uint32_t staged_row) { return (int)((staged_row >> kPanelClassShift) & (kDies - 1)); }
+constexpr int kPanelRowShift = 24;       // panel entry code = (row inside the workgroup << 24) | staged head row
 
 struct LevelImage {
   int64_t n_i = 0;
@@ -85,6 +94,12 @@ struct LevelImage {
   size_t off_wrow_mid = 0;   // uint32 n_wrows : entries before it read X rows, the rest index the LDS window
   size_t off_wrow_y = 0;     // int32  n_wrows
   size_t off_wrow_win = 0;   // uint32 n_wrows : first position of the row's tile window
+  // head panels: head rows whose head-block entries are swept window by window with the rows'
+  // accumulators resident in LDS; their entries follow the window entries in the entry array.
+  // Workgroup w = group * kDies + class owns bins [w * kPanelBins, (w + 1) * kPanelBins).
+  int64_t n_panel_rows = 0, n_panel_groups = 0, n_panel_bins = 0, nnz_panel = 0;
+  size_t off_panel_ptr = 0;  // uint32 n_panel_bins + 1 (entry offsets; a bin is one lane group's stream)
+  size_t off_panel_y = 0;    // int32  n_panel_groups * kPanelRows : Y row of every accumulator, -1 = unused
   int64_t map_offset = 0;    // first element of this level in the entry map (one uint32 per entry, image order)
 };
 
@@ -105,6 +120,8 @@ struct PackOptions {
   int32_t class_min = 32;     // a row is split by class when it holds classes * class_min entries
   int32_t piece_max = 48;     // a class piece with at most this many entries is a group-list item
   int32_t stage_head = 1;     // gather the head rows of level 0 into a contiguous buffer
+  int32_t panel = 0;          // run the head block of sparse head rows in panels (accumulators in LDS, one column class per die)
+  int32_t panel_min = 8;      // fewest head-block entries of a row that joins a panel
   int32_t window_span = 2048; // widest column span of an LDS-window tile (0 = no such tiles)
   int32_t window_tile_rows = 1024;  // most rows per tile
   double window_reuse = 8.0;  // a tile is kept when its diagonal-block entries >= this x span
@@ -117,6 +134,7 @@ struct Image {
   int64_t max_partials = 0;
   int64_t max_stage_rows = 0;
   int64_t max_window_span = 0;
+  int64_t max_panel_slots = 0;       // most panel accumulators (groups * kPanelRows) of a level
   std::vector<uint32_t> entry_src;   // per entry in image order: its index in the caller's CSR arrays
 };
 
@@ -148,6 +166,16 @@ int launch_reduce(const uint32_t* split_ptr, const int32_t* split_y, int64_t n_s
                   const float* partials, float* Y, int32_t k, bool accumulate, void* stream);
 int launch_gather(const int32_t* perm, int64_t n_i, const float* X, float* Xp, int32_t k,
                   void* stream);
+// Head panels.  launch_panel: every workgroup (group, class) sums its entries times rows of the
+// staged head Xh into LDS accumulators and stores them to part[class][slot][0:k].
+// launch_panel_combine: Y[panel_y[slot]] += sum over the kDies classes, in class order.
+int launch_panel(const uint32_t* panel_ptr, const int32_t* panel_y, const Entry* entries,
+                 int64_t n_groups, const float* Xh, int64_t xh_rows, float* part, int32_t k, void* stream);
+int launch_panel_combine(const int32_t* panel_y, int64_t n_slots, const float* part, float* Y, int32_t k,
+                         void* stream);
+int launch_sddmm_panel(const uint32_t* panel_ptr, const int32_t* panel_y, const Entry* entries,
+                       const uint32_t* emap, int64_t n_bins, const float* U, const float* Vh,
+                       int64_t vh_rows, float* S, int32_t k, void* stream);
 // max_span = widest window of the tiles (sizes the LDS allocation and the column slice)
 int launch_window(const WindowTile* tiles, int64_t n_tiles, int64_t max_span, const uint32_t* wrow_ptr,
                   const uint32_t* wrow_mid, const int32_t* wrow_y, const Entry* entries,

@@ -222,7 +222,8 @@ int decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const flo
       if (!done) {
         std::vector<int32_t> cand(order);
         std::nth_element(cand.begin(), cand.begin() + b, cand.end(), by_degree);
-        std::sort(cand.begin(), cand.begin() + b, by_degree);
+        if (opt.head_by_id) std::sort(cand.begin(), cand.begin() + b);
+        else std::sort(cand.begin(), cand.begin() + b, by_degree);
         std::vector<uint8_t> in_head(n, 0);
         for (int64_t p = 0; p < b; ++p) { L.perm[p] = cand[p]; in_head[cand[p]] = 1; }
         // the rest: the given arrangement, or a traversal of what is left without the head --

@@ -440,7 +440,7 @@ __global__ __launch_bounds__(kBlock) void sddmm_rows_kernel(
           }
           const float dot = group_reduce<NB, LPR>(p, l);
           const uint32_t mine = j + (uint32_t)(l / SPAN);
-          if (l % SPAN == 0 && mine < j_hi) S[emap[b0 + mine]] = grp[mine % SG].val * dot;
+          if (l % SPAN == 0 && mine < j_hi) S[emap ? emap[b0 + mine] : b0 + mine] = grp[mine % SG].val * dot;
         }
       }
       strip_sync();
@@ -511,10 +511,197 @@ __global__ __launch_bounds__(kBlock) void sddmm_chunks_kernel(
         }
         const float dot = group_reduce<NB, LPR>(p, l);
         const uint32_t idx = (s + (uint32_t)(l / SPAN)) * G + g;
-        if (l % SPAN == 0 && idx < nb) S[emap[b0 + idx]] = mine[idx].val * dot;
+        if (l % SPAN == 0 && idx < nb) S[emap ? emap[b0 + idx] : b0 + idx] = mine[idx].val * dot;
       }
       strip_sync();
     }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// panel kernel: workgroup w = group * 8 + class keeps the accumulators of the group's kPanelRows
+// head rows (one column slice of LPR * VEC columns) in LDS and runs on accelerator die w mod 8, so
+// its entries -- those of the group whose staged head row is of that class -- only touch the
+// die's eighth of the staged head.  Each of its kPanelBins lane groups streams one entry list,
+// ordered by column window, then row: products are summed in registers while the row stays the
+// same and added to the row's LDS accumulator when it changes (all class entries of a row are in
+// one stream, so only one lane group ever touches an accumulator and no barrier is needed while
+// streaming).  At the end the accumulators go to part[class][slot]; the combine kernel adds the
+// eight class results of a row to Y in class order.
+// ---------------------------------------------------------------------------
+#ifdef ARROW_PANEL_TRACE
+__device__ unsigned long long g_panel_trace[4 * 8192];
+#endif
+template <int VEC, int LPR, int U, bool SMALL>
+__global__ __launch_bounds__(kPanelBins * LPR) void panel_kernel(
+    const uint32_t* __restrict__ panel_ptr, const int32_t* __restrict__ panel_y,
+    const Entry* __restrict__ ent, int64_t n_bins, int64_t n_slots, const float* __restrict__ Xh,
+    float* __restrict__ part, int k) {
+  using V = typename Vec<VEC>::type;
+  constexpr int W = LPR * VEC;
+  constexpr uint32_t kRowMask = (1u << kPanelRowShift) - 1u;
+  constexpr int SG = 4 * LPR < 8 ? 8 : (4 * LPR > 32 ? 32 : 4 * LPR);
+  constexpr int UU = U < SG ? U : SG;
+  constexpr uint32_t kNone = 0xffffffffu;
+  __shared__ __attribute__((aligned(16))) float acc[kPanelRows * W];
+  __shared__ Entry strip[kPanelBins * SG];
+  const int tid = threadIdx.x;
+  const int l = tid % LPR;
+  const int g = tid / LPR;
+  const int c = l * VEC + blockIdx.y * W;
+  const bool col_ok = c < k;
+  const uint32_t row_bytes = 4u * (uint32_t)k;
+  const uint32_t col_bytes = col_ok ? 4u * (uint32_t)c : 0u;
+#ifdef ARROW_PANEL_TRACE
+  const unsigned wg_id = blockIdx.x + gridDim.x * blockIdx.y;
+  if (tid == 0 && wg_id < 8192) g_panel_trace[4 * wg_id] = wall_clock64();
+#endif
+  for (int i = tid; i < kPanelRows * LPR; i += kPanelBins * LPR) vstore<VEC>(acc + i * VEC, vzero<VEC>());
+  __syncthreads();
+  const int64_t bin = (int64_t)blockIdx.x * kPanelBins + g;
+  if (bin < n_bins) {
+    const uint32_t lo = panel_ptr[bin], hi = panel_ptr[bin + 1];
+    const char* base = reinterpret_cast<const char*>(Xh);
+    Entry* grp = strip + g * SG;
+    uint32_t cur = kNone;
+    V a = vzero<VEC>();
+    auto flush_to = [&](uint32_t r) {               // add the register sum to its accumulator, start row r
+      if (cur != kNone) {
+        float* ap = acc + cur * W + l * VEC;
+        V t = vload<VEC>(ap);
+        vadd(t, a);
+        vstore<VEC>(ap, t);
+      }
+      cur = r;
+      a = vzero<VEC>();
+    };
+    for (uint32_t b0 = lo; b0 < hi; b0 += SG) {
+      const uint32_t nb = hi - b0 < (uint32_t)SG ? hi - b0 : (uint32_t)SG;
+#pragma unroll
+      for (int t = 0; t < SG / LPR; ++t) {
+        const uint32_t idx = (uint32_t)(l + t * LPR);
+        if (idx < nb) grp[idx] = ent[b0 + idx];
+      }
+      strip_sync();
+      uint32_t j = 0;
+      for (; j + UU <= nb; j += UU) {               // full rounds: nothing is predicated
+        Entry e[UU];
+        V x[UU];
+#pragma unroll
+        for (int u = 0; u < UU; ++u) e[u] = grp[j + u];
+#pragma unroll
+        for (int u = 0; u < UU; ++u)
+          x[u] = load_row<VEC, SMALL>(base, (int32_t)((uint32_t)e[u].xrow & kRowMask), row_bytes, col_bytes);
+        const uint32_t r0 = (uint32_t)e[0].xrow >> kPanelRowShift;
+        const uint32_t r1 = (uint32_t)e[UU - 1].xrow >> kPanelRowShift;
+        if (r0 == r1) {                             // the stream is ordered by row: the whole round is one row
+          if (r0 != cur) flush_to(r0);
+#pragma unroll
+          for (int u = 0; u < UU; ++u) vfma(a, e[u].val, x[u]);
+        } else {
+#pragma unroll
+          for (int u = 0; u < UU; ++u) {
+            const uint32_t r = (uint32_t)e[u].xrow >> kPanelRowShift;
+            if (r != cur) flush_to(r);
+            vfma(a, e[u].val, x[u]);
+          }
+        }
+      }
+      for (; j < nb; ++j) {                         // the last, partly filled round of the stream
+        const Entry e = grp[j];
+        const V x = load_row<VEC, SMALL>(base, (int32_t)((uint32_t)e.xrow & kRowMask), row_bytes, col_bytes);
+        const uint32_t r = (uint32_t)e.xrow >> kPanelRowShift;
+        if (r != cur) flush_to(r);
+        vfma(a, e.val, x);
+      }
+      strip_sync();
+    }
+    flush_to(kNone);
+  }
+  __syncthreads();
+#ifdef ARROW_PANEL_TRACE
+  if (tid == 0 && wg_id < 8192) g_panel_trace[4 * wg_id + 2] = wall_clock64();
+#endif
+  const int64_t slot0 = (int64_t)(blockIdx.x / kDies) * kPanelRows;
+  const int32_t* py = panel_y + slot0;
+  float* out = part + ((size_t)(blockIdx.x % kDies) * (size_t)n_slots + (size_t)slot0) * (size_t)k;
+  for (int r = g; r < kPanelRows; r += kPanelBins) {
+    if (py[r] < 0 || !col_ok) continue;
+    vstore<VEC>(out + (size_t)r * (size_t)k + c, vload<VEC>(acc + r * W + l * VEC));
+  }
+}
+
+// Y[panel_y[slot]] += part[0][slot] + ... + part[7][slot], lane group per slot.
+template <int VEC, int LPR>
+__global__ __launch_bounds__(kBlock) void panel_combine_kernel(
+    const int32_t* __restrict__ panel_y, int64_t n_slots, const float* __restrict__ part,
+    float* __restrict__ Y, int k) {
+  using V = typename Vec<VEC>::type;
+  constexpr int GPB = kBlock / LPR;
+  const int64_t slot = (int64_t)blockIdx.x * GPB + threadIdx.x / LPR;
+  const int c = (threadIdx.x % LPR) * VEC + blockIdx.y * (LPR * VEC);
+  if (slot >= n_slots || c >= k) return;
+  const int32_t y = panel_y[slot];
+  if (y < 0) return;
+  V p[kDies];
+#pragma unroll
+  for (int x = 0; x < kDies; ++x)
+    p[x] = vload<VEC>(part + ((size_t)x * (size_t)n_slots + (size_t)slot) * (size_t)k + c);
+  V acc = p[0];
+#pragma unroll
+  for (int x = 1; x < kDies; ++x) vadd(acc, p[x]);
+  float* yp = Y + (size_t)y * (size_t)k + c;
+  vadd(acc, vload<VEC>(yp));
+  vstore<VEC>(yp, acc);
+}
+
+// Sampled product over the panel entries: lane group per bin, NB entries at a time; the row
+// vertex of an entry is looked up through the accumulator table.
+template <int VEC, int LPR, int NB, bool SMALL>
+__global__ __launch_bounds__(kBlock) void sddmm_panel_kernel(
+    const uint32_t* __restrict__ panel_ptr, const int32_t* __restrict__ panel_y,
+    const Entry* __restrict__ ent, const uint32_t* __restrict__ emap, int64_t n_bins,
+    const float* __restrict__ U, const float* __restrict__ Vh, float* __restrict__ S, int k,
+    int slices) {
+  using V = typename Vec<VEC>::type;
+  constexpr int GPB = kBlock / LPR;
+  constexpr int W = LPR * VEC;
+  constexpr int SPAN = LPR / NB;
+  constexpr uint32_t kRowMask = (1u << kPanelRowShift) - 1u;
+  const int l = threadIdx.x % LPR;
+  const int64_t bin = (int64_t)blockIdx.x * GPB + threadIdx.x / LPR;
+  if (bin >= n_bins) return;
+  const uint32_t lo = panel_ptr[bin], hi = panel_ptr[bin + 1];
+  const int32_t* py = panel_y + (bin / (kDies * kPanelBins)) * kPanelRows;
+  const uint32_t row_bytes = 4u * (uint32_t)k;
+  const char* base = reinterpret_cast<const char*>(Vh);
+  for (uint32_t j = lo; j < hi; j += NB) {
+    int32_t xr[NB], ur[NB];
+    float p[NB];
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+      const uint32_t code = (uint32_t)ent[j + u < hi ? j + u : lo].xrow;
+      xr[u] = (int32_t)(code & kRowMask);
+      ur[u] = py[code >> kPanelRowShift];
+      p[u] = 0.f;
+    }
+    for (int sl = 0; sl < slices; ++sl) {
+      const int c = l * VEC + sl * W;
+      const bool col_ok = c < k;
+      const uint32_t col_bytes = col_ok ? 4u * (uint32_t)c : 0u;
+      V x[NB], uu[NB];
+#pragma unroll
+      for (int u = 0; u < NB; ++u) {
+        const bool ok = j + u < hi && col_ok;
+        x[u] = ok ? load_row<VEC, SMALL>(base, xr[u], row_bytes, col_bytes) : vzero<VEC>();
+        uu[u] = ok ? vload<VEC>(U + (size_t)ur[u] * (size_t)k + c) : vzero<VEC>();
+      }
+#pragma unroll
+      for (int u = 0; u < NB; ++u) p[u] += vdot(uu[u], x[u]);
+    }
+    const float dot = group_reduce<NB, LPR>(p, l);
+    const uint32_t mine = j + (uint32_t)(l / SPAN);
+    if (l % SPAN == 0 && mine < hi) S[emap ? emap[mine] : mine] = ent[mine].val * dot;
   }
 }
 
@@ -715,7 +902,10 @@ int launch_window(const WindowTile* tiles, int64_t n_tiles, int64_t max_span, co
 }
 
 namespace {
-template <int LPR> struct BatchOf { static constexpr int value = LPR < 8 ? LPR : 8; };
+#ifndef ARROW_SDDMM_BATCH
+#define ARROW_SDDMM_BATCH 4     // entries a lane group reduces together (row loads in flight per lane)
+#endif
+template <int LPR> struct BatchOf { static constexpr int value = LPR < ARROW_SDDMM_BATCH ? LPR : ARROW_SDDMM_BATCH; };
 }  // namespace
 
 int launch_sddmm_rows(int mode, const uint32_t* item_ptr, const uint32_t* item_mid,
@@ -765,5 +955,88 @@ int launch_sddmm_chunks(const uint32_t* chunk_ptr, const uint32_t* chunk_mid, co
     return (int)hipGetLastError();
   });
 }
+
+namespace {
+// (VEC, LPR) with at most 16 lanes per row: the panel kernel runs kPanelBins lane groups per workgroup
+template <typename F>
+int dispatch_narrow(const Shape& s, F&& f) {
+#define ARROW_CASE(V, L) \
+  if (s.vec == V && s.lpr == L) return f(std::integral_constant<int, V>{}, std::integral_constant<int, L>{});
+#define ARROW_CASES(V) ARROW_CASE(V, 1) ARROW_CASE(V, 2) ARROW_CASE(V, 4) ARROW_CASE(V, 8) ARROW_CASE(V, 16)
+  ARROW_CASES(4)
+  ARROW_CASES(2)
+  ARROW_CASES(1)
+#undef ARROW_CASES
+#undef ARROW_CASE
+  return (int)hipErrorInvalidValue;
+}
+}  // namespace
+
+int launch_panel(const uint32_t* panel_ptr, const int32_t* panel_y, const Entry* entries,
+                 int64_t n_groups, const float* Xh, int64_t xh_rows, float* part, int32_t k, void* stream) {
+  if (n_groups <= 0) return 0;
+  const int vec = (k % 4 == 0) ? 4 : (k % 2 == 0) ? 2 : 1;
+#ifndef ARROW_PANEL_LANES
+#define ARROW_PANEL_LANES 16
+#endif
+  const Shape s = pick_shape(k, ARROW_PANEL_LANES * vec);   // at most 16 lanes per row: LDS rows of at most 64 floats
+  const bool small = small_matrix(xh_rows, k);
+  return dispatch_narrow(s, [&](auto Vc, auto L) -> int {
+    constexpr int VEC = decltype(Vc)::value, LPR = decltype(L)::value;
+    const int64_t blocks = n_groups * kDies;          // workgroup id mod 8 = column class = die
+    if (blocks > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
+    const int64_t n_bins = blocks * kPanelBins, n_slots = n_groups * kPanelRows;
+    dim3 grid((unsigned)blocks, (unsigned)s.slices);
+    if (small)
+      hipLaunchKernelGGL((panel_kernel<VEC, LPR, 8, true>), grid, dim3(kPanelBins * LPR), 0, (hipStream_t)stream,
+                         panel_ptr, panel_y, entries, n_bins, n_slots, Xh, part, (int)k);
+    else
+      hipLaunchKernelGGL((panel_kernel<VEC, LPR, 8, false>), grid, dim3(kPanelBins * LPR), 0, (hipStream_t)stream,
+                         panel_ptr, panel_y, entries, n_bins, n_slots, Xh, part, (int)k);
+    return (int)hipGetLastError();
+  });
+}
+
+int launch_panel_combine(const int32_t* panel_y, int64_t n_slots, const float* part, float* Y, int32_t k,
+                         void* stream) {
+  if (n_slots <= 0) return 0;
+  const Shape s = pick_shape(k, 0);
+  return dispatch_shape(s, [&](auto Vc, auto L) -> int {
+    constexpr int VEC = decltype(Vc)::value, LPR = decltype(L)::value;
+    const int64_t blocks = ceil_div(n_slots, kBlock / LPR);
+    if (blocks > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
+    dim3 grid((unsigned)blocks, (unsigned)s.slices);
+    hipLaunchKernelGGL((panel_combine_kernel<VEC, LPR>), grid, dim3(kBlock), 0, (hipStream_t)stream, panel_y,
+                       n_slots, part, Y, (int)k);
+    return (int)hipGetLastError();
+  });
+}
+
+int launch_sddmm_panel(const uint32_t* panel_ptr, const int32_t* panel_y, const Entry* entries,
+                       const uint32_t* emap, int64_t n_bins, const float* U, const float* Vh,
+                       int64_t vh_rows, float* S, int32_t k, void* stream) {
+  if (n_bins <= 0) return 0;
+  const Shape s = pick_shape(k, 0);
+  const bool small = small_matrix(vh_rows, k);
+  return dispatch_shape(s, [&](auto Vc, auto L) -> int {
+    constexpr int VEC = decltype(Vc)::value, LPR = decltype(L)::value, NB = BatchOf<LPR>::value;
+    const int64_t blocks = ceil_div(n_bins, kBlock / LPR);
+    if (blocks > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
+    dim3 grid((unsigned)blocks);
+    if (small)
+      hipLaunchKernelGGL((sddmm_panel_kernel<VEC, LPR, NB, true>), grid, dim3(kBlock), 0, (hipStream_t)stream,
+                         panel_ptr, panel_y, entries, emap, n_bins, U, Vh, S, (int)k, (int)s.slices);
+    else
+      hipLaunchKernelGGL((sddmm_panel_kernel<VEC, LPR, NB, false>), grid, dim3(kBlock), 0, (hipStream_t)stream,
+                         panel_ptr, panel_y, entries, emap, n_bins, U, Vh, S, (int)k, (int)s.slices);
+    return (int)hipGetLastError();
+  });
+}
+
+#ifdef ARROW_PANEL_TRACE
+extern "C" int arrow_debug_read_panel_trace(unsigned long long* host, size_t count) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_panel_trace), count * sizeof(unsigned long long));
+}
+#endif
 
 }  // namespace arrow

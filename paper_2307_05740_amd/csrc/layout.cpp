@@ -39,6 +39,8 @@
 #include <cmath>
 #include <cstdint>
 #include <cstring>
+#include <functional>
+#include <queue>
 
 #include "arrow.h"
 
@@ -78,6 +80,12 @@ struct Plan {
   std::vector<WindowTile> wtiles;     // diagonal-block tiles with their X window staged in LDS
   std::vector<int32_t> wrow_pos;      // row positions of the window rows, tile by tile
   std::vector<uint32_t> wrow_ptr;     // offsets of their entries (relative to the level's entries)
+  std::vector<uint32_t> skip;         // per row position: leading (head-block) entries handed to the panels
+  std::vector<int32_t> panel_pos;     // accumulator slot -> row position, -1 = unused (groups * kPanelRows)
+  std::vector<uint8_t> panel_bin;     // per (slot, class): the bin of workgroup (group, class) that streams the row's class entries
+  std::vector<uint32_t> panel_ptr;    // per bin: offsets of its entries (relative to the level's entries)
+  int64_t nnz_panel = 0, n_panel_rows = 0;
+  uint32_t row_skip(int64_t p) const { return skip.empty() ? 0u : skip[p]; }
 };
 
 // order the recs of one list: class phases as padded die queues, then the last phase in
@@ -125,6 +133,7 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
   img.max_partials = 0;
   img.max_stage_rows = 0;
   img.max_window_span = 0;
+  img.max_panel_slots = 0;
   const int64_t short_max = opt.short_max < 0 ? 0 : opt.short_max;
   const int64_t chunk_nnz = opt.chunk_nnz < 1 ? 1 : opt.chunk_nnz;
   const int64_t chunk_min = opt.chunk_min < 1 ? 1 : (opt.chunk_min > chunk_nnz ? chunk_nnz : opt.chunk_min);
@@ -209,10 +218,113 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
     for (const WindowTile& t : P.wtiles)
       if ((int64_t)t.win_count > img.max_window_span) img.max_window_span = t.win_count;
 
+    // ---- head panels ---------------------------------------------------------------------------
+    // A head row whose head-block entries are too few per column window to form window-local
+    // chunks hands them to a panel.  kPanelRows such rows form a group (groups hold equal numbers
+    // of entries).  The group's entries are dealt by column class -- staged head row mod 8 -- to 8
+    // workgroups, and workgroup (group, class) has the linear id group * 8 + class, so class c is
+    // always served by accelerator die c: a die's L2 only ever holds an eighth of the staged head
+    // X_0.  Each workgroup keeps the group's accumulators in LDS and streams its entries in
+    // kPanelBins lane-group streams of equal length, each ordered by column window, then row; a row's
+    // class entries all sit in one stream, so no two lane groups touch the same accumulator.
+    // The eight class results of a row are added to Y afterwards, in class order.
+    // What is left of such a row (columns outside the head) is planned like any other row.
+    if (opt.panel && im.staged && classes == 0 && window > 0 && im.n_stage <= (1LL << kPanelRowShift)) {
+      const int64_t n_windows = (im.n_stage + window - 1) / window;
+      const int64_t dense = chunk_min * n_windows;       // such rows fill window-local chunks by themselves
+      const int64_t pmin = opt.panel_min < 1 ? 1 : opt.panel_min;
+      std::vector<std::pair<uint32_t, int32_t>> cand;    // (head-block entries, position)
+      int64_t nnz_p = 0;
+      // a row much longer than the others cannot be balanced against them inside a workgroup's
+      // streams: the second pass also leaves out rows above 6 x the mean of the first
+      int64_t cap = dense;
+      for (int pass = 0; pass < 2; ++pass) {
+        cand.clear();
+        nnz_p = 0;
+        for (int64_t p = 0; p < head; ++p) {
+          if (taken[p]) continue;
+          const int32_t* cb = L.colpos.data() + L.rowptr[p];
+          const int32_t* ce = L.colpos.data() + L.rowptr[p + 1];
+          const int64_t cnt = std::lower_bound(cb, ce, (int32_t)im.n_stage) - cb;
+          if (cnt < pmin || cnt >= cap) continue;
+          cand.emplace_back((uint32_t)cnt, (int32_t)p);
+          nnz_p += cnt;
+        }
+        if (cand.empty()) break;
+        const int64_t lim = 6 * (nnz_p / (int64_t)cand.size()) + 1;
+        if (lim >= cap) break;
+        cap = lim;
+      }
+      // worth its launches only when the head spans several windows (else it stays in L2 anyway)
+      // and the panels hold a fair share of the level
+      if (!cand.empty() && n_windows >= 2 && (double)nnz_p >= 0.05 * (double)lev_nnz) {
+        std::sort(cand.begin(), cand.end(), [](const std::pair<uint32_t, int32_t>& x, const std::pair<uint32_t, int32_t>& y) {
+          return x.first != y.first ? x.first > y.first : x.second < y.second;
+        });
+        const int64_t n_cand = (int64_t)cand.size();
+        const int64_t n_groups = (n_cand + kPanelRows - 1) / kPanelRows;
+        P.skip.assign(L.n_i, 0);
+        P.panel_pos.assign((size_t)n_groups * kPanelRows, -1);
+        // longest row first, each to the group with the fewest entries so far that still has room
+        {
+          std::vector<int32_t> filled((size_t)n_groups, 0);
+          std::priority_queue<std::pair<int64_t, int64_t>, std::vector<std::pair<int64_t, int64_t>>,
+                              std::greater<std::pair<int64_t, int64_t>>> open;     // (entries, group)
+          for (int64_t g = 0; g < n_groups; ++g) open.emplace(0, g);
+          for (int64_t i = 0; i < n_cand; ++i) {
+            const std::pair<int64_t, int64_t> top = open.top();
+            open.pop();
+            const int64_t g = top.second;
+            P.panel_pos[(size_t)g * kPanelRows + filled[g]] = cand[i].second;
+            P.skip[cand[i].second] = cand[i].first;
+            if (++filled[g] < kPanelRows) open.emplace(top.first + cand[i].first, g);
+          }
+        }
+        // per (group, class): the rows' class entries, longest first, to the shortest stream
+        const int64_t n_bins = n_groups * kDies * kPanelBins;
+        P.panel_bin.assign((size_t)n_groups * kPanelRows * kDies, 0);
+        std::vector<uint32_t> bin_len((size_t)n_bins, 0);
+#pragma omp parallel
+        {
+          std::vector<std::pair<uint32_t, int32_t>> rows_c;   // (class entries, slot in the group)
+          std::vector<uint32_t> cls_cnt((size_t)kPanelRows * kDies);
+#pragma omp for schedule(dynamic, 4)
+          for (int64_t g = 0; g < n_groups; ++g) {
+            std::fill(cls_cnt.begin(), cls_cnt.end(), 0u);
+            for (int r = 0; r < kPanelRows; ++r) {
+              const int32_t p = P.panel_pos[(size_t)g * kPanelRows + r];
+              if (p < 0) continue;
+              const int32_t* cb = L.colpos.data() + L.rowptr[p];
+              for (uint32_t e = 0; e < P.skip[p]; ++e) ++cls_cnt[(size_t)r * kDies + panel_class((uint32_t)cb[e])];
+            }
+            for (int c = 0; c < kDies; ++c) {
+              rows_c.clear();
+              for (int r = 0; r < kPanelRows; ++r)
+                if (cls_cnt[(size_t)r * kDies + c]) rows_c.emplace_back(cls_cnt[(size_t)r * kDies + c], r);
+              std::sort(rows_c.begin(), rows_c.end(), [](const std::pair<uint32_t, int32_t>& x, const std::pair<uint32_t, int32_t>& y) {
+                return x.first != y.first ? x.first > y.first : x.second < y.second;
+              });
+              uint32_t* len = bin_len.data() + ((size_t)g * kDies + c) * kPanelBins;
+              for (const auto& rc : rows_c) {
+                int best = 0;
+                for (int j = 1; j < kPanelBins; ++j) if (len[j] < len[best]) best = j;
+                len[best] += rc.first;
+                P.panel_bin[((size_t)g * kPanelRows + rc.second) * kDies + c] = (uint8_t)best;
+              }
+            }
+          }
+        }
+        P.panel_ptr.assign((size_t)n_bins + 1, 0);       // lengths for now; offsets once the lists are placed
+        for (int64_t bi = 0; bi < n_bins; ++bi) P.panel_ptr[bi + 1] = bin_len[bi];
+        P.nnz_panel = nnz_p;
+        P.n_panel_rows = n_cand;
+      }
+    }
+
     // ---- short rows / long rows -------------------------------------------------------------
     for (int64_t p = 0; p < L.n_i; ++p) {
       if (taken[p]) continue;
-      const int64_t len = L.rowptr[p + 1] - L.rowptr[p];
+      const int64_t len = L.rowptr[p + 1] - L.rowptr[p] - P.row_skip(p);
       if (len > short_max) { P.long_rows.push_back((int32_t)p); continue; }
       if (len == 0 && li > 0) continue;
       P.row_pos.push_back((int32_t)p);
@@ -228,8 +340,8 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
 #pragma omp for schedule(dynamic, 64)
       for (int64_t r = 0; r < n_long; ++r) {
         const int32_t p = P.long_rows[r];
-        const int64_t len = L.rowptr[p + 1] - L.rowptr[p];
-        const int32_t* cols = L.colpos.data() + L.rowptr[p];
+        const int64_t len = L.rowptr[p + 1] - L.rowptr[p] - P.row_skip(p);
+        const int32_t* cols = L.colpos.data() + L.rowptr[p] + P.row_skip(p);
         std::vector<Rec>& out = per_row[r];
         if (classes > 0 && len >= classes * class_min) {
           // split by column class; where every part starts is found by a second scan
@@ -281,6 +393,15 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
               if (len - e0 < (chunk_min + 1) / 2) e0 = len;        // absorb a small tail
             }
             const int64_t piece = e0 - s0;
+            if (piece <= piece_max) {                              // a lane group is enough for it
+              Rec rc;
+              rc.row = p; rc.len = (uint32_t)piece; rc.dst = 0;
+              rc.phase = class_phases;
+              rc.queue = -1; rc.list = 0; rc.key = (uint32_t)(cols[s0] / key_window); rc.seq = 0;
+              out.push_back(rc);
+              s0 = e0;
+              continue;
+            }
             const int64_t parts = (piece + chunk_nnz - 1) / chunk_nnz;
             const int64_t base = piece / parts, extra = piece % parts;
             int64_t at_row = s0;
@@ -356,17 +477,26 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
           ptr.push_back((uint32_t)at);
           dst.push_back(L.perm[p]);
           irow.push_back(L.perm[p]);
-          at += L.rowptr[p + 1] - L.rowptr[p];
+          at += L.rowptr[p + 1] - L.rowptr[p] - P.row_skip(p);
           ++real_items[0];
         }
       }
       ptr.push_back((uint32_t)at);
       list_nnz[list] = at - at0;
     }
-    if (at + nnz_w != lev_nnz) { err = "work lists do not cover the level"; return ARROW_EINTERNAL; }
+    if (at + nnz_w + P.nnz_panel != lev_nnz) { err = "work lists do not cover the level"; return ARROW_EINTERNAL; }
     P.wrow_ptr.reserve(P.wrow_pos.size() + 1);
     for (int32_t p : P.wrow_pos) { P.wrow_ptr.push_back((uint32_t)at); at += L.rowptr[p + 1] - L.rowptr[p]; }
     P.wrow_ptr.push_back((uint32_t)at);
+    if (!P.panel_pos.empty()) {
+      const int64_t n_bins = (int64_t)P.panel_ptr.size() - 1;
+      for (int64_t bi = 0; bi < n_bins; ++bi) {
+        const uint32_t len = P.panel_ptr[bi + 1];
+        P.panel_ptr[bi] = (uint32_t)at;
+        at += len;
+      }
+      P.panel_ptr[n_bins] = (uint32_t)at;
+    }
 
     // ---- staged head: buffer rows in class-major order ------------------------------------------
     if (im.staged) {
@@ -397,6 +527,11 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
     im.n_wtiles = (int64_t)P.wtiles.size();
     im.n_wrows = (int64_t)P.wrow_pos.size();
     im.nnz_w = nnz_w;
+    im.n_panel_rows = P.n_panel_rows;
+    im.n_panel_groups = (int64_t)P.panel_pos.size() / kPanelRows;
+    im.n_panel_bins = im.n_panel_groups * kDies * kPanelBins;
+    if (im.n_panel_groups * kPanelRows > img.max_panel_slots) img.max_panel_slots = im.n_panel_groups * kPanelRows;
+    im.nnz_panel = P.nnz_panel;
     if (slots > img.max_partials) img.max_partials = slots;
 
     im.off_perm = total;        total = align_up(total + sizeof(int32_t) * (size_t)L.n_i);
@@ -416,6 +551,8 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
     im.off_wrow_mid = total;    total = align_up(total + sizeof(uint32_t) * (size_t)im.n_wrows);
     im.off_wrow_y = total;      total = align_up(total + sizeof(int32_t) * (size_t)im.n_wrows);
     im.off_wrow_win = total;    total = align_up(total + sizeof(uint32_t) * (size_t)im.n_wrows);
+    im.off_panel_ptr = total;   total = align_up(total + sizeof(uint32_t) * (size_t)(im.n_panel_bins + 1));
+    im.off_panel_y = total;     total = align_up(total + sizeof(int32_t) * (size_t)im.n_panel_groups * kPanelRows);
     im.off_entries = total;     total = align_up(total + sizeof(Entry) * (size_t)lev_nnz);
     im.map_offset = map_total;  map_total += lev_nnz;
     img.levels.push_back(im);
@@ -473,7 +610,7 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
 #pragma omp parallel for schedule(dynamic, 4096)
     for (int64_t r = 0; r < n_plain; ++r) {
       const int32_t p = P.row_pos[r];
-      int64_t src = L.rowptr[p];
+      int64_t src = L.rowptr[p] + P.row_skip(p);
       const int64_t slot = P.piece_slots + r;
       for (uint32_t e = P.list_ptr[0][slot]; e < P.list_ptr[0][slot + 1]; ++e, ++src) {
         ent[e].xrow = L.perm[L.colpos[src]];
@@ -491,8 +628,8 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
 #pragma omp for schedule(dynamic, 16)
       for (int64_t r = 0; r < n_long; ++r) {
         const int32_t p = P.long_rows[r];
-        const int64_t len = L.rowptr[p + 1] - L.rowptr[p];
-        const int64_t src0 = L.rowptr[p];
+        const int64_t len = L.rowptr[p + 1] - L.rowptr[p] - P.row_skip(p);
+        const int64_t src0 = L.rowptr[p] + P.row_skip(p);
         const int32_t* cols = L.colpos.data() + src0;
         const int64_t rec0 = P.row_first[r], rec1 = P.row_first[r + 1];
         const int64_t* seq = nullptr;
@@ -554,6 +691,46 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
             emap[e] = L.src[src];
           }
           wmid[wr] = mid;
+        }
+      }
+    }
+    // head panels: per workgroup (group, class) the class entries of the group's rows, dealt to
+    // the streams chosen above; inside a stream ordered by row, then column (the kernel relies on
+    // the rows of a stream never going backwards)
+    if (im.n_panel_bins) {
+      std::memcpy(base + im.off_panel_ptr, P.panel_ptr.data(), sizeof(uint32_t) * P.panel_ptr.size());
+      int32_t* py = reinterpret_cast<int32_t*>(base + im.off_panel_y);
+      for (size_t s = 0; s < P.panel_pos.size(); ++s) py[s] = P.panel_pos[s] < 0 ? -1 : L.perm[P.panel_pos[s]];
+      const int64_t n_groups = im.n_panel_groups;
+#pragma omp parallel
+      {
+        // (stream, row in the group, column) -> level entry
+        std::vector<std::pair<uint64_t, int64_t>> keys;
+#pragma omp for schedule(dynamic, 4)
+        for (int64_t g = 0; g < n_groups; ++g) {
+          for (int c = 0; c < kDies; ++c) {
+            keys.clear();
+            for (int r = 0; r < kPanelRows; ++r) {
+              const int32_t p = P.panel_pos[(size_t)g * kPanelRows + r];
+              if (p < 0) continue;
+              const uint64_t bin = P.panel_bin[((size_t)g * kPanelRows + r) * kDies + c];
+              for (int64_t src = L.rowptr[p]; src < L.rowptr[p] + P.skip[p]; ++src) {
+                const uint64_t q = (uint64_t)L.colpos[src];
+                if (panel_class((uint32_t)q) != c) continue;
+                keys.emplace_back((bin << 56) | ((uint64_t)r << 24) | (q & 0xffffffu), src);
+              }
+            }
+            std::sort(keys.begin(), keys.end());
+            uint32_t e = P.panel_ptr[((size_t)g * kDies + c) * kPanelBins];
+            for (const auto& kv : keys) {
+              const uint32_t lrow = (uint32_t)((kv.first >> 24) & 0xffu);
+              const int32_t q = L.colpos[kv.second];
+              ent[e].xrow = (int32_t)((lrow << kPanelRowShift) | (uint32_t)stage_row(q));
+              ent[e].val = L.vals[kv.second];
+              emap[e] = L.src[kv.second];
+              ++e;
+            }
+          }
         }
       }
     }
@@ -699,6 +876,47 @@ int verify_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, con
       }
     }
     if (wexpect != (uint32_t)im.n_wrows) { err = "window rows not covered by tiles"; return ARROW_EINTERNAL; }
+    // head panels: streams cover their entries in order; an entry names a used accumulator of its
+    // group and a staged head row of its workgroup's column class; all entries of one
+    // (accumulator, class) sit in one stream; windows never go backwards inside a stream
+    if (im.n_panel_bins) {
+      const uint32_t* pp = reinterpret_cast<const uint32_t*>(base + im.off_panel_ptr);
+      const int32_t* py = reinterpret_cast<const int32_t*>(base + im.off_panel_y);
+      if (im.n_panel_bins != im.n_panel_groups * kDies * kPanelBins || !im.staged || im.classes != 0) { err = "bad panel geometry"; return ARROW_EINTERNAL; }
+      std::vector<uint8_t> row_seen((size_t)n, 0);
+      for (int64_t s = 0; s < im.n_panel_groups * kPanelRows; ++s) {
+        if (py[s] == -1) continue;
+        if (py[s] < 0 || py[s] >= n || row_seen[py[s]]) { err = "panel accumulator names a bad or repeated Y row"; return ARROW_EINTERNAL; }
+        row_seen[py[s]] = 1;
+      }
+      std::vector<int32_t> owner((size_t)kPanelRows);
+      for (int64_t wg = 0; wg < im.n_panel_groups * kDies; ++wg) {
+        std::fill(owner.begin(), owner.end(), -1);
+        const uint32_t cls = (uint32_t)(wg % kDies);
+        for (int j = 0; j < kPanelBins; ++j) {
+          const int64_t bin = wg * kPanelBins + j;
+          const uint32_t lo = pp[bin], hi = pp[bin + 1];
+          if (lo != expect || hi < lo || (int64_t)hi > lev_nnz) { err = "panel stream offsets out of order"; return ARROW_EINTERNAL; }
+          expect = hi;
+          for (uint32_t e = lo; e < hi; ++e) {
+            const uint32_t code = (uint32_t)ent[e].xrow;
+            const uint32_t lrow = code >> kPanelRowShift, xs = code & ((1u << kPanelRowShift) - 1);
+            if (lrow >= (uint32_t)kPanelRows) { err = "panel entry outside its group's accumulators"; return ARROW_EINTERNAL; }
+            if (e > lo && lrow < ((uint32_t)ent[e - 1].xrow >> kPanelRowShift)) { err = "panel stream rows go backwards"; return ARROW_EINTERNAL; }
+            if (owner[lrow] >= 0 && owner[lrow] != j) { err = "two panel streams share an accumulator"; return ARROW_EINTERNAL; }
+            owner[lrow] = j;
+            const int32_t y = py[(wg / kDies) * kPanelRows + lrow];
+            if (y < 0) { err = "panel entry names an unused accumulator"; return ARROW_EINTERNAL; }
+            if ((int64_t)xs >= im.n_stage || (uint32_t)panel_class(xs) != cls) { err = "panel entry: staged row out of range or of another class"; return ARROW_EINTERNAL; }
+            const int64_t xr = stage_perm[xs];
+            if (xr < 0 || xr >= n) { err = "X row out of range"; return ARROW_EINTERNAL; }
+            checksum[y] += (double)ent[e].val * (double)(1 + xr);
+            ent_row[e] = y;
+          }
+          covered += hi - lo;
+        }
+      }
+    }
     {
       // the map sends every image entry to a nonzero of this level with the same value and row
       std::vector<uint32_t> order((size_t)lev_nnz);

@@ -212,6 +212,9 @@ def test_error_paths():
     dict(ARROW_WINDOW_ROWS="64", ARROW_CHUNK_MIN="5", ARROW_CHUNK_NNZ="40"),
     dict(ARROW_WINDOW_SPAN="0"), dict(ARROW_WINDOW_SPAN="4096", ARROW_WINDOW_REUSE_X10="1"),
     dict(ARROW_WINDOW_REUSE_X10="20", ARROW_WINDOW_SHARE_X1000="0"),
+    dict(ARROW_PANEL="1", ARROW_WINDOW_ROWS="32", ARROW_PANEL_MIN="1", ARROW_SHORT_MAX="0"),
+    dict(ARROW_PANEL="1", ARROW_WINDOW_ROWS="128", ARROW_CHUNK_MIN="16", ARROW_HEAD_BY_ID="0"),
+    dict(ARROW_WINDOW_ROWS="64", ARROW_HEAD_BY_ID="0"),
 ])
 def test_packed_image_self_check_under_pack_options(monkeypatch, env):
     for name, v in env.items():
@@ -223,6 +226,80 @@ def test_packed_image_self_check_under_pack_options(monkeypatch, env):
             binding.arrow_self_check(h)
         finally:
             binding.arrow_destroy(h)
+
+
+@pytest.mark.parametrize("env", [dict(), dict(ARROW_PANEL="1", ARROW_WINDOW_ROWS="64"),
+                                 dict(ARROW_CLASSES="8", ARROW_CLASS_MIN="2", ARROW_CLASS_GRAN="16")])
+def test_entry_map_is_a_bijection_onto_the_nonzeros(monkeypatch, env):
+    for name, v in env.items():
+        monkeypatch.setenv(name, v)
+    w = synth.make_config(0)
+    h = binding.arrow_decompose(w.rowptr, w.colidx, w.vals, w.b)
+    try:
+        emap = binding.arrow_export_entry_map(h)
+        assert emap.shape == (w.nnz,) and np.array_equal(np.sort(emap), np.arange(w.nnz, dtype=np.uint32))
+        # level by level the map's image is that level's set of nonzeros (as (row, column, value))
+        at = 0
+        csr_row = np.repeat(np.arange(w.n), np.diff(w.rowptr))
+        for i in range(binding.arrow_info(h)["levels"]):
+            perm, r, c, v = binding.arrow_export_level(h, i)
+            src = np.sort(emap[at:at + len(v)])
+            at += len(v)
+            want = np.lexsort((perm[c], perm[r]))
+            got = np.lexsort((w.colidx[src], csr_row[src]))
+            assert np.array_equal(csr_row[src][got], perm[r][want])
+            assert np.array_equal(w.colidx[src][got], perm[c][want])
+            assert np.array_equal(w.vals[src][got].view(np.uint32), v[want].view(np.uint32))
+        assert at == w.nnz
+    finally:
+        binding.arrow_destroy(h)
+
+
+def test_head_order_inside_the_head(monkeypatch):
+    """The arrow shape only fixes WHICH vertices are in the head; inside it they sit in id order
+    (so that position order follows the caller's column order), or by falling degree on request.
+    Both give the same head set and the same level sizes."""
+    w = synth.make_config(0)
+    h = binding.arrow_decompose(w.rowptr, w.colidx, w.vals, w.b)
+    head_id = binding.arrow_export_level(h, 0)[0][:w.b]
+    nnz_id = [binding.arrow_level_info(h, i)["nnz"] for i in range(binding.arrow_info(h)["levels"])]
+    binding.arrow_destroy(h)
+    assert np.all(np.diff(head_id) > 0)
+    monkeypatch.setenv("ARROW_HEAD_BY_ID", "0")
+    h = binding.arrow_decompose(w.rowptr, w.colidx, w.vals, w.b)
+    head_deg = binding.arrow_export_level(h, 0)[0][:w.b]
+    nnz_deg = [binding.arrow_level_info(h, i)["nnz"] for i in range(binding.arrow_info(h)["levels"])]
+    binding.arrow_destroy(h)
+    assert not np.all(np.diff(head_deg) > 0)
+    assert np.array_equal(np.sort(head_deg), head_id) and nnz_id[0] == nnz_deg[0]
+
+
+def test_head_panels_take_the_sparse_head_rows(monkeypatch):
+    """With windows of 64 positions the head of width 512 spans 8 of them: head rows with fewer
+    than chunk_min * 8 head-block entries hand those entries to panels, the rest stays in chunks."""
+    monkeypatch.setenv("ARROW_WINDOW_ROWS", "64")
+    monkeypatch.setenv("ARROW_PANEL", "1")
+    w = synth.make_config(0)
+    h = binding.arrow_decompose(w.rowptr, w.colidx, w.vals, w.b)
+    try:
+        binding.arrow_self_check(h)
+        li = binding.arrow_level_info(h, 0)
+        perm, r, c, v = binding.arrow_export_level(h, 0)
+        hh = np.bincount(r[(r < w.b) & (c < w.b)], minlength=w.b)
+        want = (hh >= 8) & (hh < 64 * 8)
+        cap = 6 * (hh[want].sum() // np.count_nonzero(want)) + 1     # rows far above the mean stay in chunks
+        if cap < 64 * 8:
+            want = (hh >= 8) & (hh < cap)
+        assert li["panel_rows"] == np.count_nonzero(want) and li["nnz_panel"] == hh[want].sum()
+        assert li["panel_bins"] % 256 == 0 and li["panel_bins"] >= li["panel_rows"]   # 8 x 32 streams per 256 rows
+        assert li["nnz_rows"] + li["nnz_chunks"] + li["nnz_window"] + li["nnz_panel"] == li["nnz"]
+        assert binding.arrow_level_info(h, 1)["panel_rows"] == 0        # later levels stage no head
+    finally:
+        binding.arrow_destroy(h)
+    monkeypatch.setenv("ARROW_PANEL", "0")
+    h = binding.arrow_decompose(w.rowptr, w.colidx, w.vals, w.b)
+    assert binding.arrow_level_info(h, 0)["panel_rows"] == 0
+    binding.arrow_destroy(h)
 
 
 def test_save_and_load_round_trip(tmp_path, monkeypatch):

@@ -139,6 +139,45 @@ def test_die_queues_and_head_staging(torch, monkeypatch, env, k):
         op.close()
 
 
+@pytest.mark.parametrize("env", [
+    dict(ARROW_WINDOW_ROWS="64"),
+    dict(ARROW_WINDOW_ROWS="32", ARROW_PANEL_MIN="1", ARROW_SHORT_MAX="0"),
+    dict(ARROW_WINDOW_ROWS="128", ARROW_CHUNK_MIN="16"),
+    dict(ARROW_WINDOW_ROWS="64", ARROW_HEAD_BY_ID="0"),
+])
+@pytest.mark.parametrize("k", [1, 3, 6, 16, 36, 64, 128, 130, 260])
+def test_head_panels(torch, monkeypatch, env, k):
+    """Head rows whose head-block entries run in panels (accumulators in LDS, added to Y last);
+    small windows make the head span several of them so that panels are formed."""
+    monkeypatch.setenv("ARROW_PANEL", "1")
+    for name, v in env.items():
+        monkeypatch.setenv(name, v)
+    w = synth.make_config(0)
+    X = synth.normal_matrix(w.n, k, seed=77 + k)
+    op, Xd, Y = run_product(torch, csr_of(w), w.b, X)
+    lv = op.levels()
+    assert lv[0]["panel_rows"] > 0 and lv[0]["nnz_panel"] > 0
+    Yref, B = oracle.spmm(*csr_of(w), X)
+    assert_within(Y, Yref, B)
+    Y2 = op.spmm(Xd).cpu().numpy()
+    assert np.array_equal(Y.view(np.uint32), Y2.view(np.uint32))
+    op.close()
+
+
+def test_head_panels_larger_operand_and_chained(torch, monkeypatch):
+    monkeypatch.setenv("ARROW_PANEL", "1")
+    monkeypatch.setenv("ARROW_WINDOW_ROWS", "64")
+    w = synth.make_config(4, shrink=8)              # Chung-Lu, 65536 vertices, k = 32, A^5
+    X = w.make_x()
+    op = binding.ArrowSpMM(*csr_of(w), w.b)
+    assert op.levels()[0]["panel_rows"] > 256       # several workgroups of panels
+    Xd = torch.from_numpy(X).cuda()
+    op.spmm_iter(Xd, w.l)
+    Xl, El = oracle.spmm_iter(*csr_of(w), X, w.l)
+    assert_within(Xd.cpu().numpy(), Xl, El, scale=w.l)
+    op.close()
+
+
 def test_grid_one_level(torch):
     w = synth.make_config(1, shrink=4)              # 256 x 256 grid, k = 32, b = 4096
     X = w.make_x()

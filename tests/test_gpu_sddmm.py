@@ -138,6 +138,47 @@ def test_window_rows(torch, monkeypatch, k):
     op.close()
 
 
+@pytest.mark.parametrize("env", [
+    dict(ARROW_WINDOW_ROWS="64"),
+    dict(ARROW_WINDOW_ROWS="32", ARROW_PANEL_MIN="1", ARROW_SHORT_MAX="0"),
+])
+@pytest.mark.parametrize("k", [1, 3, 16, 36, 128, 260, 1030])
+def test_head_panels(torch, monkeypatch, env, k):
+    """Entries that the product runs in head panels: their row is found through the panel table."""
+    monkeypatch.setenv("ARROW_PANEL", "1")
+    for name, v in env.items():
+        monkeypatch.setenv(name, v)
+    w = synth.make_config(0)
+    U = synth.normal_matrix(w.n, k, seed=81 + k)
+    V = synth.normal_matrix(w.n, k, seed=82 + k)
+    op, _, _, S = run_sampled(torch, csr_of(w), w.b, U, V)
+    assert op.levels()[0]["nnz_panel"] > 0
+    Sref, B = oracle.sddmm(*csr_of(w), U, V)
+    assert_within(S, Sref, B)
+    op.close()
+
+
+@pytest.mark.parametrize("env", [dict(), dict(ARROW_PANEL="1", ARROW_WINDOW_ROWS="64")])
+def test_image_order_output(torch, monkeypatch, env):
+    """Option "sddmm_image_order": contiguous stores; the exported entry map brings S back to CSR order."""
+    for name, v in env.items():
+        monkeypatch.setenv(name, v)
+    w = synth.make_config(0)
+    U = synth.normal_matrix(w.n, 36, seed=11)
+    V = synth.normal_matrix(w.n, 36, seed=12)
+    op, Ud, Vd, S = run_sampled(torch, csr_of(w), w.b, U, V)
+    binding.arrow_set_option(op.h, "sddmm_image_order", 1)
+    Simg = op.sddmm(Ud, Vd, torch.full((w.nnz,), float("nan"), device="cuda")).cpu().numpy()
+    emap = binding.arrow_export_entry_map(op.h)
+    back = np.empty_like(Simg)
+    back[emap] = Simg
+    assert np.array_equal(back.view(np.uint32), S.view(np.uint32))
+    binding.arrow_set_option(op.h, "sddmm_image_order", 0)
+    S2 = op.sddmm(Ud, Vd).cpu().numpy()
+    assert np.array_equal(S2.view(np.uint32), S.view(np.uint32))
+    op.close()
+
+
 def test_several_levels_and_hub_row(torch):
     # a hub adjacent to everything plus a sparse random remainder: long split row, several levels
     rng = np.random.default_rng(33)
