@@ -79,6 +79,33 @@ def test_config3_rmat_s23_k128_sampled_rows(torch):
     want = ata @ X.astype(np.float64)
     scale = np.abs(ata) @ np.abs(X.astype(np.float64))
     assert np.all(np.abs(colsum.cpu().numpy() - want) <= 1e-5 * scale)
+
+    # the sampled dense-dense product on the same handle: S = A .* (U V^T), U = X
+    print("sampled product ...", flush=True)
+    V = synth.normal_matrix(w.n, w.k, seed=w.seed_x + 1)
+    Vd = torch.from_numpy(V).cuda()
+    Sd = torch.full((w.nnz,), float("nan"), dtype=torch.float32, device="cuda")
+    op.sddmm(Xd, Vd, Sd)
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(Sd).any())              # every element of S was written
+    # the operand restricted to the sampled rows (all other rows empty), so the oracle's output
+    # is the sampled rows' entries in CSR order
+    cnt = np.zeros(w.n, np.int64)
+    cnt[rows] = deg[rows]
+    rp = np.concatenate([[0], np.cumsum(cnt)])
+    first = np.cumsum(deg[rows]) - deg[rows]
+    idx = np.repeat(w.rowptr[rows] - first, deg[rows]) + np.arange(int(deg[rows].sum()), dtype=np.int64)
+    print(f"oracle on {len(idx)} sampled entries ...", flush=True)
+    Sref, Bs = oracle.sddmm(rp, w.colidx[idx], w.vals[idx], X, V)
+    Ss = Sd[torch.from_numpy(idx).cuda()].cpu().numpy()
+    check(Ss, Sref, Bs)
+    # a property that holds at any size: sum_p S[p] = sum_i <U[i], (A V)[i]>, scaled by the same
+    # product with |U|, |V| (a bound on sum_p |a_p| <|U[i]|, |V[j]|> up to fp32 rounding)
+    op.spmm(Vd, Yd)
+    lhs = float(Sd.double().sum())
+    rhs = float((Xd.double() * Yd.double()).sum())
+    Sa = op.sddmm(Xd.abs(), Vd.abs())
+    assert abs(lhs - rhs) <= 2e-5 * float(Sa.double().abs().sum())
     op.close()
 
 
