@@ -22,6 +22,9 @@
 //                   several chunks, in a fixed order, and scatters to Y
 //   window kernel - diagonal-block tiles with their window of P_i X staged in LDS
 //   gather kernel - rows of P_i X materialised (the staged head X_0, or a whole level)
+//   panel kernels - optional: head-block entries of sparse head rows with the rows'
+//                   accumulators in LDS, one column class per accelerator die
+//   sddmm kernels - the sampled dense-dense product S = A .* (U V^T) over the same lists
 // Both product kernels fetch their entries with one coalesced load per batch,
 // park them in a wavefront-private LDS strip and read them back per lane
 // group, so that U row loads are in flight before the first FMA; the SIMDs
@@ -529,9 +532,6 @@ __global__ __launch_bounds__(kBlock) void sddmm_chunks_kernel(
 // streaming).  At the end the accumulators go to part[class][slot]; the combine kernel adds the
 // eight class results of a row to Y in class order.
 // ---------------------------------------------------------------------------
-#ifdef ARROW_PANEL_TRACE
-__device__ unsigned long long g_panel_trace[4 * 8192];
-#endif
 template <int VEC, int LPR, int U, bool SMALL>
 __global__ __launch_bounds__(kPanelBins * LPR) void panel_kernel(
     const uint32_t* __restrict__ panel_ptr, const int32_t* __restrict__ panel_y,
@@ -552,10 +552,6 @@ __global__ __launch_bounds__(kPanelBins * LPR) void panel_kernel(
   const bool col_ok = c < k;
   const uint32_t row_bytes = 4u * (uint32_t)k;
   const uint32_t col_bytes = col_ok ? 4u * (uint32_t)c : 0u;
-#ifdef ARROW_PANEL_TRACE
-  const unsigned wg_id = blockIdx.x + gridDim.x * blockIdx.y;
-  if (tid == 0 && wg_id < 8192) g_panel_trace[4 * wg_id] = wall_clock64();
-#endif
   for (int i = tid; i < kPanelRows * LPR; i += kPanelBins * LPR) vstore<VEC>(acc + i * VEC, vzero<VEC>());
   __syncthreads();
   const int64_t bin = (int64_t)blockIdx.x * kPanelBins + g;
@@ -619,9 +615,6 @@ __global__ __launch_bounds__(kPanelBins * LPR) void panel_kernel(
     flush_to(kNone);
   }
   __syncthreads();
-#ifdef ARROW_PANEL_TRACE
-  if (tid == 0 && wg_id < 8192) g_panel_trace[4 * wg_id + 2] = wall_clock64();
-#endif
   const int64_t slot0 = (int64_t)(blockIdx.x / kDies) * kPanelRows;
   const int32_t* py = panel_y + slot0;
   float* out = part + ((size_t)(blockIdx.x % kDies) * (size_t)n_slots + (size_t)slot0) * (size_t)k;
@@ -902,10 +895,9 @@ int launch_window(const WindowTile* tiles, int64_t n_tiles, int64_t max_span, co
 }
 
 namespace {
-#ifndef ARROW_SDDMM_BATCH
-#define ARROW_SDDMM_BATCH 4     // entries a lane group reduces together (row loads in flight per lane)
-#endif
-template <int LPR> struct BatchOf { static constexpr int value = LPR < ARROW_SDDMM_BATCH ? LPR : ARROW_SDDMM_BATCH; };
+// entries a lane group reduces together (= row loads in flight per lane); 4 measured best of 4, 8, 16
+constexpr int kSddmmBatch = 4;
+template <int LPR> struct BatchOf { static constexpr int value = LPR < kSddmmBatch ? LPR : kSddmmBatch; };
 }  // namespace
 
 int launch_sddmm_rows(int mode, const uint32_t* item_ptr, const uint32_t* item_mid,
@@ -976,10 +968,7 @@ int launch_panel(const uint32_t* panel_ptr, const int32_t* panel_y, const Entry*
                  int64_t n_groups, const float* Xh, int64_t xh_rows, float* part, int32_t k, void* stream) {
   if (n_groups <= 0) return 0;
   const int vec = (k % 4 == 0) ? 4 : (k % 2 == 0) ? 2 : 1;
-#ifndef ARROW_PANEL_LANES
-#define ARROW_PANEL_LANES 16
-#endif
-  const Shape s = pick_shape(k, ARROW_PANEL_LANES * vec);   // at most 16 lanes per row: LDS rows of at most 64 floats
+  const Shape s = pick_shape(k, 16 * vec);         // at most 16 lanes per row: LDS rows of at most 64 floats
   const bool small = small_matrix(xh_rows, k);
   return dispatch_narrow(s, [&](auto Vc, auto L) -> int {
     constexpr int VEC = decltype(Vc)::value, LPR = decltype(L)::value;
@@ -1033,10 +1022,5 @@ int launch_sddmm_panel(const uint32_t* panel_ptr, const int32_t* panel_y, const 
   });
 }
 
-#ifdef ARROW_PANEL_TRACE
-extern "C" int arrow_debug_read_panel_trace(unsigned long long* host, size_t count) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_panel_trace), count * sizeof(unsigned long long));
-}
-#endif
 
 }  // namespace arrow
