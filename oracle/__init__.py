@@ -4,7 +4,7 @@ Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
 ``bench.py`` may import this package.  It shares no code with the GPU library
 and imports nothing from it.
 
-* :func:`spmm`, :func:`spmm_iter`, :func:`sddmm` -- ctypes wrappers of ``spmm_oracle.c``
+* :func:`spmm`, :func:`spmm_iter`, :func:`sddmm`, :func:`mttkrp` -- ctypes wrappers of ``spmm_oracle.c``
   (plain CSR loops in fp64 over the original, undecomposed operand).
 * :mod:`oracle.arrow_checks` -- host-side checks of a decomposition
   (bit-exact reassembly, arrow shape, injective permutations) and a slow
@@ -36,6 +36,8 @@ def _load():
         lib.oracle_spmm_iter.argtypes = [i64, vp, vp, vp, vp, i32, i32, vp, vp]
         lib.oracle_sddmm.restype = ctypes.c_int
         lib.oracle_sddmm.argtypes = [i64, vp, vp, vp, vp, vp, i32, vp, vp]
+        lib.oracle_mttkrp.restype = ctypes.c_int
+        lib.oracle_mttkrp.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, vp, vp, i32, vp, vp]
         lib.oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -109,6 +111,28 @@ def sddmm(rowptr, colidx, vals, U, V):
     if rc != 0:
         raise RuntimeError(f"oracle_sddmm failed ({rc})")
     return S, B
+
+
+def mttkrp(dims, ti, tj, tk, tv, B, C):
+    """fp64 ``A(i, a) = sum_{j,k} T(i,j,k) B(j,a) C(k,a)`` over the coordinate list of T and its
+    bound ``sum |T| |B| |C|``.  Returns ``(A, E)``, float64 arrays of shape (I, R)."""
+    I, J, K = (int(d) for d in dims)
+    ti = np.ascontiguousarray(ti, dtype=np.int32)
+    tj = np.ascontiguousarray(tj, dtype=np.int32)
+    tk = np.ascontiguousarray(tk, dtype=np.int32)
+    tv = np.ascontiguousarray(tv, dtype=np.float32)
+    assert ti.shape == tj.shape == tk.shape == tv.shape and ti.ndim == 1
+    for M, rows in ((B, J), (C, K)):
+        assert M.dtype == np.float32 and M.ndim == 2 and M.flags.c_contiguous and M.shape[0] == rows
+    assert B.shape[1] == C.shape[1]
+    R = B.shape[1]
+    A = np.empty((I, R), dtype=np.float64)
+    E = np.empty((I, R), dtype=np.float64)
+    rc = _load().oracle_mttkrp(I, J, K, ti.shape[0], ti.ctypes.data, tj.ctypes.data, tk.ctypes.data,
+                               tv.ctypes.data, B.ctypes.data, C.ctypes.data, R, A.ctypes.data, E.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"oracle_mttkrp failed ({rc})")
+    return A, E
 
 
 def num_threads() -> int:

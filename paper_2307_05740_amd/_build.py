@@ -54,9 +54,9 @@ def build_synth() -> str:
 
 
 def build_oracle() -> str:
-    src = os.path.join(REPO_DIR, "oracle", "spmm_oracle.c")
+    srcs = [os.path.join(REPO_DIR, "oracle", f) for f in ("spmm_oracle.c", "mttkrp_oracle.c")]
     _run(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
-          "-ffp-contract=off", "-o", ORACLE_LIB, src, "-lm"])
+          "-ffp-contract=off", "-o", ORACLE_LIB] + srcs + ["-lm"])
     return ORACLE_LIB
 
 

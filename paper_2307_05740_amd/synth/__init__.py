@@ -189,3 +189,91 @@ def make_config(index: int, shrink: int = 0) -> Workload:
         return Workload(f"chunglu_n{n}_k32_pow5", n, rp, ci, fill_row_normalized(rp), 32,
                         max(262144 >> s, 8), 5, SEED_X + 4)
     raise ValueError("config index must be 0..4")
+
+
+# ---------------------------------------------------------------------------------------------
+# order-3 sparse tensors (inputs of the MTTKRP kernel); pure numpy, counter-based
+# ---------------------------------------------------------------------------------------------
+SEED_TENSOR = SEED_GRAPH + 3000
+
+
+def _mix64(x: np.ndarray) -> np.ndarray:
+    """splitmix64 finaliser on a uint64 array (wrap-around arithmetic)."""
+    with np.errstate(over="ignore"):
+        x = x + np.uint64(0x9E3779B97F4A7C15)
+        x = (x ^ (x >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+        x = (x ^ (x >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+        return x ^ (x >> np.uint64(31))
+
+
+def _unit(seed: int, counter: np.ndarray, stream: int) -> np.ndarray:
+    """Uniform [0, 1) doubles keyed by (seed, counter, stream): 53 random bits each."""
+    with np.errstate(over="ignore"):
+        h = _mix64(_mix64(counter * np.uint64(4) + np.uint64(stream)) ^ np.uint64(seed))
+    return (h >> np.uint64(11)).astype(np.float64) * (1.0 / (1 << 53))
+
+
+def tensor3(dims, samples: int, seed: int = SEED_TENSOR, skew=(1.0, 1.0, 1.0), block: int = 1 << 24):
+    """Sparse I x J x K tensor from ``samples`` seeded index triples (duplicates merged).
+
+    Index m of a triple is ``floor(dim_m * u ** skew_m)`` with u uniform: skew 1 is the uniform
+    tensor of a given density, skew > 1 concentrates entries on low indices (hub slices and
+    long fibres, as in real multi-way data).  Values are uniform in [-1, 1), keyed by the triple.
+    Returns ``(i, j, k, vals)`` sorted by (i, j, k): int32, int32, int32, float32.
+    """
+    I, J, K = (int(d) for d in dims)
+    assert max(I, J, K) < (1 << 21) and min(I, J, K) >= 1 and samples >= 0
+    keys = []
+    for t0 in range(0, samples, block):
+        t = np.arange(t0, min(samples, t0 + block), dtype=np.uint64)
+        idx = []
+        for m, (d, a) in enumerate(zip((I, J, K), skew)):
+            u = _unit(seed, t, m)
+            idx.append(np.minimum((d * (u ** a if a != 1.0 else u)).astype(np.uint64), np.uint64(d - 1)))
+        keys.append((idx[0] << np.uint64(42)) | (idx[1] << np.uint64(21)) | idx[2])
+    key = np.unique(np.concatenate(keys)) if keys else np.zeros(0, np.uint64)
+    i = (key >> np.uint64(42)).astype(np.int32)
+    j = ((key >> np.uint64(21)) & np.uint64((1 << 21) - 1)).astype(np.int32)
+    k = (key & np.uint64((1 << 21) - 1)).astype(np.int32)
+    with np.errstate(over="ignore"):
+        h = _mix64(key ^ np.uint64(seed + 77))
+    vals = ((h >> np.uint64(40)).astype(np.float64) * (2.0 / (1 << 24)) - 1.0).astype(np.float32)
+    return i, j, k, vals
+
+
+@dataclass
+class TensorWorkload:
+    """One order-3 MTTKRP configuration: COO tensor sorted by (i, j, k) and the rank R."""
+    name: str
+    dims: tuple
+    i: np.ndarray
+    j: np.ndarray
+    k: np.ndarray
+    vals: np.ndarray
+    R: int
+    seed_f: int
+
+    @property
+    def nnz(self) -> int:
+        return int(self.vals.shape[0])
+
+    def factors(self):
+        """The two dense factor matrices B (J x R) and C (K x R), standard normal."""
+        return (normal_matrix(self.dims[1], self.R, self.seed_f),
+                normal_matrix(self.dims[2], self.R, self.seed_f + 1))
+
+
+def make_tensor_config(index: int, shrink: int = 0) -> TensorWorkload:
+    """Order-3 workloads: 0 = uniform, density 0.1 %, side 4096 >> shrink, R = 64 (the shape of
+    the paper's synthetic scaling tensors at half their side); 1 = skewed indices (hub slices,
+    long fibres), 2^20 x 2^17 x 2^17 >> shrink with 64 M samples, R = 64."""
+    s = int(shrink)
+    if index == 0:
+        d = max(4096 >> s, 8)
+        i, j, k, v = tensor3((d, d, d), int(round(1e-3 * d ** 3)), SEED_TENSOR + 0)
+        return TensorWorkload(f"tensor3_uniform_{d}_d0.001_R64", (d, d, d), i, j, k, v, 64, SEED_X + 10)
+    if index == 1:
+        dims = (max((1 << 20) >> s, 8), max((1 << 17) >> s, 8), max((1 << 17) >> s, 8))
+        i, j, k, v = tensor3(dims, (64 << 20) >> (2 * s) if s < 13 else 64, SEED_TENSOR + 1, skew=(3.0, 2.0, 1.5))
+        return TensorWorkload(f"tensor3_skewed_{dims[0]}x{dims[1]}x{dims[2]}_R64", dims, i, j, k, v, 64, SEED_X + 11)
+    raise ValueError("tensor config index must be 0..1")

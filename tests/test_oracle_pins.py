@@ -273,3 +273,121 @@ def test_sddmm_closed_forms_and_library():
     lhs = np.add.reduceat(np.concatenate([S, [0.0]]), np.minimum(w.rowptr[:-1], len(S)))[:n]
     lhs[np.diff(w.rowptr) == 0] = 0.0
     assert np.all(np.abs(lhs - np.sum(U.astype(np.float64) * Y, axis=1)) <= 1e-11 * (1 + np.abs(lhs)))
+
+
+# ---------------------------------------------------------------------------------------------
+# order-3 MTTKRP  A(i,a) = sum_{j,k} T(i,j,k) B(j,a) C(k,a)
+# ---------------------------------------------------------------------------------------------
+def random_tensor(rng, dims, density):
+    I, J, K = dims
+    M = rng.random(dims) < density
+    i, j, k = np.nonzero(M)                                   # sorted by (i, j, k)
+    v = rng.uniform(-1, 1, len(i)).astype(np.float32)
+    return i.astype(np.int32), j.astype(np.int32), k.astype(np.int32), v
+
+
+def test_mttkrp_golden_hand_2x2x2():
+    rec = {}
+    for line in open(os.path.join(GOLDEN, "hand_2x2x2_mttkrp.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, *nums = line.split()
+        rec[name] = np.array([float(t) for t in nums])
+    A, E = oracle.mttkrp((2, 2, 2), rec["T_i"], rec["T_j"], rec["T_k"], rec["T_v"],
+                         rec["B"].reshape(2, 2).astype(np.float32), rec["C"].reshape(2, 2).astype(np.float32))
+    assert np.array_equal(A, rec["A"].reshape(2, 2)) and np.array_equal(E, rec["E"].reshape(2, 2))
+
+
+def test_mttkrp_exact_rational_brute_force():
+    rng = np.random.default_rng(41)
+    dims, R = (4, 5, 3), 3
+    i, j, k, v = random_tensor(rng, dims, 0.4)
+    B = rng.standard_normal((dims[1], R)).astype(np.float32)
+    C = rng.standard_normal((dims[2], R)).astype(np.float32)
+    A, E = oracle.mttkrp(dims, i, j, k, v, B, C)
+    u = 2.0 ** -53
+    for ii in range(dims[0]):
+        for a in range(R):
+            s = Fraction(0); e = Fraction(0)
+            for p in range(len(v)):
+                if i[p] == ii:
+                    t = Fraction(float(v[p])) * Fraction(float(B[j[p], a])) * Fraction(float(C[k[p], a]))
+                    s += t; e += abs(t)
+            m = dims[1] * dims[2]
+            assert abs(Fraction(A[ii, a]) - s) <= Fraction((m + 3) * u) * e
+            assert abs(Fraction(E[ii, a]) - e) <= Fraction((m + 3) * u) * e
+
+
+def test_mttkrp_library_contraction_and_pairwise_form():
+    rng = np.random.default_rng(42)
+    dims, R = (13, 9, 11), 6
+    i, j, k, v = random_tensor(rng, dims, 0.2)
+    B = rng.standard_normal((dims[1], R)).astype(np.float32)
+    C = rng.standard_normal((dims[2], R)).astype(np.float32)
+    A, E = oracle.mttkrp(dims, i, j, k, v, B, C)
+    T = np.zeros(dims); T[i, j, k] = v
+    want = np.einsum("ijk,ja,ka->ia", T, B.astype(np.float64), C.astype(np.float64))
+    assert np.all(np.abs(A - want) <= 1e-13 * E + 1e-300)
+    assert np.all(np.abs(E - np.einsum("ijk,ja,ka->ia", np.abs(T), np.abs(B, dtype=np.float64), np.abs(C, dtype=np.float64))) <= 1e-13 * E)
+    # the pairwise (factorized) evaluation gives the same result: X(i,j,a) = sum_k T C, A = sum_j X B
+    X = np.einsum("ijk,ka->ija", T, C.astype(np.float64))
+    assert np.all(np.abs(A - np.einsum("ija,ja->ia", X, B.astype(np.float64))) <= 1e-13 * E + 1e-300)
+    # the entry order of the list does not matter beyond rounding (unsorted lists run on one thread)
+    perm = rng.permutation(len(v))
+    A2, E2 = oracle.mttkrp(dims, i[perm], j[perm], k[perm], v[perm], B, C)
+    assert np.all(np.abs(A2 - A) <= 1e-13 * E + 1e-300)
+
+
+def test_mttkrp_closed_forms():
+    rng = np.random.default_rng(43)
+    I, J, K, R = 6, 7, 5, 4
+    B = rng.standard_normal((J, R)).astype(np.float32)
+    C = rng.standard_normal((K, R)).astype(np.float32)
+    # all-ones dense tensor: A(i,a) = (sum_j B(j,a)) (sum_k C(k,a))
+    ii, jj, kk = np.meshgrid(np.arange(I), np.arange(J), np.arange(K), indexing="ij")
+    A, _ = oracle.mttkrp((I, J, K), ii.ravel(), jj.ravel(), kk.ravel(), np.ones(I * J * K, np.float32), B, C)
+    want = B.astype(np.float64).sum(0) * C.astype(np.float64).sum(0)
+    assert np.allclose(A, np.broadcast_to(want, (I, R)), rtol=1e-12, atol=1e-12)
+    # indicator factors: B = ones, C = identity (K = R) -> A(i,a) = sum_j T(i,j,a), exactly
+    i, j, k, v = random_tensor(rng, (I, J, R), 0.5)
+    A, E = oracle.mttkrp((I, J, R), i, j, k, v, np.ones((J, R), np.float32), np.eye(R, dtype=np.float32))
+    T = np.zeros((I, J, R)); T[i, j, k] = v
+    assert np.allclose(A, T.sum(1), rtol=0, atol=1e-15) and np.allclose(E, np.abs(T).sum(1), rtol=0, atol=1e-15)
+
+
+def test_mttkrp_reduces_to_the_matrix_product_when_K_is_1():
+    """K = 1 and C = ones: A = T_(IxJ) . B, the order-2 kernel -- checked against the other checker."""
+    w = synth.make_config(0, shrink=3)
+    rows = np.repeat(np.arange(w.n), np.diff(w.rowptr)).astype(np.int32)
+    B = synth.normal_matrix(w.n, 5, seed=9)
+    A, E = oracle.mttkrp((w.n, w.n, 1), rows, w.colidx, np.zeros(w.nnz, np.int32), w.vals, B, np.ones((1, 5), np.float32))
+    Y, Bd = oracle.spmm(w.rowptr, w.colidx, w.vals, B)
+    assert np.array_equal(A, Y) and np.array_equal(E, Bd)
+
+
+def test_mttkrp_swapping_modes_and_factors():
+    rng = np.random.default_rng(44)
+    dims, R = (5, 6, 6), 3
+    i, j, k, v = random_tensor(rng, dims, 0.3)
+    B = rng.standard_normal((6, R)).astype(np.float32)
+    C = rng.standard_normal((6, R)).astype(np.float32)
+    A, E = oracle.mttkrp(dims, i, j, k, v, B, C)
+    A_sw, _ = oracle.mttkrp(dims, i, k, j, v, C, B)          # swap the roles of j and k consistently
+    assert np.all(np.abs(A_sw - A) <= 1e-13 * E + 1e-300)
+    A_bad, _ = oracle.mttkrp(dims, i, j, k, v, C, B)         # factors swapped, indices not
+    assert not np.allclose(A_bad, A, atol=1e-3)
+    with pytest.raises(RuntimeError):
+        oracle.mttkrp(dims, i, j, k + 1, v, B, C)            # an index out of range
+
+
+def test_tensor_generator_is_seeded_sorted_and_deduplicated():
+    a = synth.make_tensor_config(0, shrink=5)
+    b = synth.make_tensor_config(0, shrink=5)
+    assert all(np.array_equal(x, y) for x, y in zip((a.i, a.j, a.k, a.vals), (b.i, b.j, b.k, b.vals)))
+    key = (a.i.astype(np.int64) * a.dims[1] + a.j) * a.dims[2] + a.k
+    assert np.all(np.diff(key) > 0)
+    assert 0.9e-3 < a.nnz / np.prod([float(d) for d in a.dims]) < 1.1e-3
+    assert np.all(np.abs(a.vals) <= 1) and abs(float(a.vals.mean())) < 0.05
+    s = synth.make_tensor_config(1, shrink=5)
+    sl = np.bincount(s.i, minlength=s.dims[0])
+    assert sl.max() > 50 * max(1.0, sl.mean()) and (sl == 0).sum() > 0.3 * s.dims[0]   # hub slices, empty slices
