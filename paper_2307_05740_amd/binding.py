@@ -27,6 +27,8 @@ EXPORTED = [
     "arrow_level_info", "arrow_export_level", "arrow_self_check", "arrow_set_option", "arrow_set_profiling",
     "arrow_get_profile", "arrow_get_level_profile", "arrow_save", "arrow_load", "arrow_last_error",
     "arrow_destroy",
+    "csf3_build", "csf3_device_bytes", "csf3_upload", "csf3_workspace_bytes", "csf3_set_workspace",
+    "csf3_mttkrp", "csf3_info", "csf3_last_error", "csf3_destroy",
 ]
 
 
@@ -58,6 +60,12 @@ class arrow_profile_t(ctypes.Structure):
                 ("rows_launches", "chunks_launches", "reduce_launches", "stage_launches",
                  "window_launches")] + \
                [("panel_ms", ctypes.c_float), ("panel_launches", ctypes.c_int32)]
+
+
+class csf3_info_t(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_int64) for name in
+                ("I", "J", "K", "nnz", "slices", "fibers", "segments", "items", "split_rows", "partials",
+                 "distinct_j", "distinct_k")] + [("build_seconds", ctypes.c_double)]
 
 
 def lib():
@@ -118,6 +126,24 @@ def lib():
     L.arrow_last_error.argtypes = []
     L.arrow_destroy.restype = None
     L.arrow_destroy.argtypes = [vp]
+    L.csf3_build.restype = ctypes.c_int
+    L.csf3_build.argtypes = [i64, i64, i64, i64, vp, vp, vp, vp, ctypes.POINTER(vp)]
+    L.csf3_device_bytes.restype = sz
+    L.csf3_device_bytes.argtypes = [vp]
+    L.csf3_upload.restype = ctypes.c_int
+    L.csf3_upload.argtypes = [vp, vp, sz, vp]
+    L.csf3_workspace_bytes.restype = sz
+    L.csf3_workspace_bytes.argtypes = [vp, i32]
+    L.csf3_set_workspace.restype = ctypes.c_int
+    L.csf3_set_workspace.argtypes = [vp, vp, sz]
+    L.csf3_mttkrp.restype = ctypes.c_int
+    L.csf3_mttkrp.argtypes = [vp, vp, vp, vp, i32, vp]
+    L.csf3_info.restype = ctypes.c_int
+    L.csf3_info.argtypes = [vp, ctypes.POINTER(csf3_info_t)]
+    L.csf3_last_error.restype = ctypes.c_char_p
+    L.csf3_last_error.argtypes = []
+    L.csf3_destroy.restype = None
+    L.csf3_destroy.argtypes = [vp]
     _lib = L
     return L
 
@@ -339,6 +365,112 @@ class ArrowSpMM:
         if self.h:
             self._torch.cuda.synchronize(self.device)
             arrow_destroy(self.h)
+            self.h = 0
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+# ---------------------------------------------------------------------------------------------
+# order-3 MTTKRP (include/csf3.h)
+# ---------------------------------------------------------------------------------------------
+def _check3(rc: int) -> None:
+    if rc != 0:
+        raise ArrowError(rc, lib().csf3_last_error().decode())
+
+
+def csf3_last_error() -> str:
+    return lib().csf3_last_error().decode()
+
+
+def csf3_build(dims, ti: np.ndarray, tj: np.ndarray, tk: np.ndarray, tv: np.ndarray) -> int:
+    """Host coordinate list (int32 i, j, k; float32 values) -> opaque handle (an integer address)."""
+    ti = np.ascontiguousarray(ti, dtype=np.int32)
+    tj = np.ascontiguousarray(tj, dtype=np.int32)
+    tk = np.ascontiguousarray(tk, dtype=np.int32)
+    tv = np.ascontiguousarray(tv, dtype=np.float32)
+    assert ti.shape == tj.shape == tk.shape == tv.shape and ti.ndim == 1
+    out = ctypes.c_void_p()
+    _check3(lib().csf3_build(int(dims[0]), int(dims[1]), int(dims[2]), ti.shape[0], ti.ctypes.data,
+                             tj.ctypes.data, tk.ctypes.data, tv.ctypes.data, ctypes.byref(out)))
+    return out.value
+
+
+def csf3_device_bytes(h: int) -> int:
+    return int(lib().csf3_device_bytes(h))
+
+
+def csf3_upload(h: int, dev_ptr: int, nbytes: int, stream: int = 0) -> None:
+    _check3(lib().csf3_upload(h, dev_ptr, nbytes, stream))
+
+
+def csf3_workspace_bytes(h: int, R: int) -> int:
+    return int(lib().csf3_workspace_bytes(h, R))
+
+
+def csf3_set_workspace(h: int, dev_ptr: int, nbytes: int) -> None:
+    _check3(lib().csf3_set_workspace(h, dev_ptr, nbytes))
+
+
+def csf3_mttkrp(h: int, b_ptr: int, c_ptr: int, a_ptr: int, R: int, stream: int = 0) -> None:
+    _check3(lib().csf3_mttkrp(h, b_ptr, c_ptr, a_ptr, R, stream))
+
+
+def csf3_info(h: int) -> dict:
+    out = csf3_info_t()
+    _check3(lib().csf3_info(h, ctypes.byref(out)))
+    return {f: getattr(out, f) for f, _ in out._fields_}
+
+
+def csf3_destroy(h: int) -> None:
+    lib().csf3_destroy(h)
+
+
+class Csf3Mttkrp:
+    """One order-3 tensor bound to torch-owned device memory (plumbing only)."""
+
+    def __init__(self, dims, ti, tj, tk, tv, device="cuda:0"):
+        import torch
+        self._torch = torch
+        self.device = torch.device(device)
+        self.h = csf3_build(dims, ti, tj, tk, tv)
+        self.info = csf3_info(self.h)
+        nbytes = csf3_device_bytes(self.h)
+        with torch.cuda.device(self.device):
+            self._image = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
+            csf3_upload(self.h, self._image.data_ptr(), self._image.numel(), self._stream())
+            torch.cuda.current_stream().synchronize()
+        self._ws = None
+        self._ws_R = 0
+
+    def _stream(self) -> int:
+        return self._torch.cuda.current_stream(self.device).cuda_stream
+
+    def mttkrp(self, B, C, A=None):
+        torch = self._torch
+        for M, rows in ((B, self.info["J"]), (C, self.info["K"])):
+            assert M.is_cuda and M.dtype == torch.float32 and M.dim() == 2 and M.is_contiguous()
+            assert M.shape[0] == rows
+        assert B.shape[1] == C.shape[1]
+        R = B.shape[1]
+        if A is None:
+            A = torch.empty((self.info["I"], R), dtype=torch.float32, device=self.device)
+        assert A.shape == (self.info["I"], R) and A.dtype == torch.float32 and A.is_contiguous()
+        if self._ws is None or self._ws_R < R:
+            torch.cuda.current_stream(self.device).synchronize()
+            self._ws = torch.empty(csf3_workspace_bytes(self.h, R), dtype=torch.uint8, device=self.device)
+            self._ws_R = R
+            csf3_set_workspace(self.h, self._ws.data_ptr(), self._ws.numel())
+        csf3_mttkrp(self.h, B.data_ptr(), C.data_ptr(), A.data_ptr(), R, self._stream())
+        return A
+
+    def close(self) -> None:
+        if self.h:
+            self._torch.cuda.synchronize(self.device)
+            csf3_destroy(self.h)
             self.h = 0
 
     def __del__(self):

@@ -1,0 +1,105 @@
+// HIP kernel for gfx950 of the order-3 MTTKRP
+//     A(i, a) = sum_{j,k} T(i, j, k) B(j, a) C(k, a)
+// in the factorize-and-fuse form (the paper's sections "Pairwise Contraction" and "Performance
+// Evaluation"): per fibre (i, j) the sum x(a) = sum_k T(i,j,k) C(k,a) is formed first -- the same
+// scaled vector update over the dense index as the matrix product's leaf -- and then multiplied
+// elementwise by B(j, :) and added to the slice's accumulator, so the intermediate never leaves
+// registers and the products with B are paid per fibre, not per entry.
+//
+// A lane owns VEC consecutive columns of the rank index, LPR lanes cover a slice of LPR * VEC
+// columns, a wavefront holds G = 64 / LPR lane groups.  One wavefront per work item (a run of
+// segments of one slice i); its lane groups take the item's segments round-robin, each segment
+// being at most 64 entries of one fibre; at the end the lane groups are combined with wavefront
+// shuffles and the result goes to row i of A or, for a slice cut into several items, to a partial
+// vector that the reduction kernel sums in a fixed order.  No atomics.
+#include <hip/hip_runtime.h>
+
+#include <climits>
+#include <cstdint>
+
+#include "arrow_internal.h"
+#include "kernel_common.h"
+
+namespace arrow {
+namespace {
+
+__device__ __forceinline__ void vmuladd(float& a, float x, float b) { a = fmaf(x, b, a); }
+__device__ __forceinline__ void vmuladd(float2& a, float2 x, float2 b) {
+  a.x = fmaf(x.x, b.x, a.x); a.y = fmaf(x.y, b.y, a.y);
+}
+__device__ __forceinline__ void vmuladd(float4& a, float4 x, float4 b) {
+  a.x = fmaf(x.x, b.x, a.x); a.y = fmaf(x.y, b.y, a.y); a.z = fmaf(x.z, b.z, a.z); a.w = fmaf(x.w, b.w, a.w);
+}
+
+template <int VEC, int LPR, int U, bool SMALL_B, bool SMALL_C>
+__global__ __launch_bounds__(kBlock) void mttkrp_kernel(
+    const uint32_t* __restrict__ item_seg, const int32_t* __restrict__ item_dst,
+    const uint32_t* __restrict__ seg_ptr, const int32_t* __restrict__ seg_j,
+    const Entry* __restrict__ ent, int64_t n_items, const float* __restrict__ B,
+    const float* __restrict__ C, float* __restrict__ A, float* __restrict__ partials, int R) {
+  using V = typename Vec<VEC>::type;
+  constexpr int G = 64 / LPR;
+  constexpr int WPB = kBlock / 64;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / 64));
+  const int64_t it = (int64_t)blockIdx.x * WPB + wave;
+  if (it >= n_items) return;            // whole wavefront leaves together
+  const uint32_t s_lo = item_seg[it], s_hi = item_seg[it + 1];
+  const int lane = threadIdx.x % 64;
+  const int g = lane / LPR;
+  const int c = (lane % LPR) * VEC + blockIdx.y * (LPR * VEC);
+  const bool col_ok = c < R;
+  const uint32_t row_bytes = 4u * (uint32_t)R;
+  const uint32_t col_bytes = col_ok ? 4u * (uint32_t)c : 0u;   // lanes past the last column read column 0
+  const char* Bb = reinterpret_cast<const char*>(B);
+  const char* Cb = reinterpret_cast<const char*>(C);
+  V acc = vzero<VEC>();
+  for (uint32_t s = s_lo + g; s < s_hi; s += G) {
+    const uint32_t lo = seg_ptr[s], hi = seg_ptr[s + 1];
+    const V b = load_row<VEC, SMALL_B>(Bb, seg_j[s], row_bytes, col_bytes);
+    V x = vzero<VEC>();
+    for (uint32_t p = lo; p < hi; p += U) {
+      Entry e[U];
+      V cr[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) e[u] = ent[p + u < hi ? p + u : hi - 1];   // one request per lane group
+#pragma unroll
+      for (int u = 0; u < U; ++u) cr[u] = load_row<VEC, SMALL_C>(Cb, e[u].xrow, row_bytes, col_bytes);
+#pragma unroll
+      for (int u = 0; u < U; ++u) vfma(x, p + u < hi ? e[u].val : 0.f, cr[u]);
+    }
+    vmuladd(acc, x, b);
+  }
+#pragma unroll
+  for (int m = LPR; m < 64; m <<= 1) vadd(acc, vshfl_xor(acc, m));
+  if (g == 0 && col_ok) {
+    const int32_t dst = item_dst[it];
+    if (dst >= 0) vstore<VEC>(A + (size_t)dst * (size_t)R + c, acc);
+    else vstore<VEC>(partials + (size_t)(-1 - dst) * (size_t)R + c, acc);
+  }
+}
+
+}  // namespace
+
+int launch_mttkrp(const uint32_t* item_seg, const int32_t* item_dst, const uint32_t* seg_ptr,
+                  const int32_t* seg_j, const Entry* entries, int64_t n_items, const float* B,
+                  int64_t b_rows, const float* C, int64_t c_rows, float* A, float* partials, int32_t R,
+                  void* stream) {
+  if (n_items <= 0) return 0;
+  const Shape s = pick_shape(R, 0);
+  const bool small_b = small_matrix(b_rows, R), small_c = small_matrix(c_rows, R);
+  return dispatch_shape(s, [&](auto Vc, auto L) -> int {
+    constexpr int VEC = decltype(Vc)::value, LPR = decltype(L)::value;
+    const int64_t blocks = ceil_div(n_items, kBlock / 64);
+    if (blocks > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
+    dim3 grid((unsigned)blocks, (unsigned)s.slices);
+#define ARROW_LAUNCH(SB, SC)                                                                        \
+  hipLaunchKernelGGL((mttkrp_kernel<VEC, LPR, 8, SB, SC>), grid, dim3(kBlock), 0, (hipStream_t)stream, \
+                     item_seg, item_dst, seg_ptr, seg_j, entries, n_items, B, C, A, partials, (int)R)
+    if (small_b && small_c) ARROW_LAUNCH(true, true);
+    else ARROW_LAUNCH(false, false);
+#undef ARROW_LAUNCH
+    return (int)hipGetLastError();
+  });
+}
+
+}  // namespace arrow

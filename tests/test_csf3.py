@@ -1,0 +1,71 @@
+"""Host side of the order-3 MTTKRP: the compressed-sparse-fibre build and its error paths (no GPU)."""
+import numpy as np
+import pytest
+
+from paper_2307_05740_amd import binding, synth
+
+
+def build_info(dims, i, j, k, v):
+    h = binding.csf3_build(dims, i, j, k, v)
+    try:
+        return binding.csf3_info(h), binding.csf3_device_bytes(h), binding.csf3_workspace_bytes(h, 8)
+    finally:
+        binding.csf3_destroy(h)
+
+
+@pytest.mark.parametrize("idx,shrink", [(0, 4), (0, 6), (1, 5), (1, 7)])
+def test_structure_counts(idx, shrink):
+    w = synth.make_tensor_config(idx, shrink)
+    info, nbytes, ws = build_info(w.dims, w.i, w.j, w.k, w.vals)
+    assert (info["I"], info["J"], info["K"]) == tuple(w.dims) and info["nnz"] == w.nnz
+    assert info["slices"] == len(np.unique(w.i))
+    fib = w.i.astype(np.int64) * w.dims[1] + w.j
+    flen = np.unique(fib, return_counts=True)[1]
+    assert info["fibers"] == len(flen)
+    assert info["segments"] == int(np.sum((flen + 63) // 64))          # fibres cut into runs of <= 64
+    sl = np.bincount(w.i, minlength=w.dims[0])
+    assert info["items"] >= w.dims[0]                                   # every slice, empty ones too
+    assert info["split_rows"] <= np.count_nonzero(sl > 64) and info["partials"] >= 2 * info["split_rows"]
+    assert info["items"] == w.dims[0] - info["split_rows"] + info["partials"]
+    assert info["distinct_j"] == len(np.unique(w.j)) and info["distinct_k"] == len(np.unique(w.k))
+    assert nbytes >= 8 * w.nnz and ws >= 32 * info["partials"]
+
+
+def test_entry_order_does_not_change_the_structure():
+    w = synth.make_tensor_config(1, 6)
+    a = build_info(w.dims, w.i, w.j, w.k, w.vals)[0]
+    p = np.random.default_rng(3).permutation(w.nnz)
+    b = build_info(w.dims, w.i[p], w.j[p], w.k[p], w.vals[p])[0]
+    for key in a:
+        if key != "build_seconds":
+            assert a[key] == b[key], key
+
+
+def test_empty_tensor_and_duplicates():
+    z = np.zeros(0, np.int32)
+    info = build_info((5, 4, 3), z, z, z, np.zeros(0, np.float32))[0]
+    assert info["nnz"] == 0 and info["items"] == 5 and info["segments"] == 0 and info["partials"] == 0
+    i = np.array([1, 1, 1], np.int32); j = np.array([2, 2, 2], np.int32); k = np.array([0, 0, 1], np.int32)
+    info = build_info((3, 3, 2), i, j, k, np.ones(3, np.float32))[0]
+    assert info["nnz"] == 3 and info["fibers"] == 1 and info["slices"] == 1      # duplicates are kept
+
+
+def test_error_paths():
+    i = np.array([0, 1], np.int32)
+    v = np.ones(2, np.float32)
+    for dims, (a, b, c) in (((2, 2, 2), (i, i, i + 1)), ((2, 2, 2), (i - 1, i, i)), ((0, 2, 2), (i, i, i)),
+                            ((2, 1, 2), (i, i, i))):
+        with pytest.raises(binding.ArrowError) as e:
+            binding.csf3_build(dims, a, b, c, v)
+        assert e.value.code == binding.ARROW_EINVAL and binding.csf3_last_error()
+    h = binding.csf3_build((2, 2, 2), i, i, i, v)
+    with pytest.raises(binding.ArrowError) as e:            # no image on the device yet
+        binding.csf3_mttkrp(h, 16, 32, 48, 4, 0)
+    assert e.value.code == binding.ARROW_ENOTREADY
+    with pytest.raises(binding.ArrowError):
+        binding.csf3_upload(h, 0, 1 << 20, 0)
+    with pytest.raises(binding.ArrowError):
+        binding.csf3_set_workspace(h, 4, 1 << 20)           # misaligned
+    assert binding.csf3_workspace_bytes(h, 0) == 0
+    binding.csf3_destroy(h)
+    binding.csf3_destroy(0)
