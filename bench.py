@@ -72,6 +72,110 @@ def algorithmic_bytes(levels, n, k):
     return per, path
 
 
+def bench_mttkrp(args, torch, binding, synth, dev) -> int:
+    """One step = one order-3 MTTKRP A = T x (B, C) through ``csf3_mttkrp`` (fibre kernel +
+    reduction of split slices), tensor image and factor matrices resident in HBM."""
+    cfg = args.config if args.config in (0, 1) else 0
+    t0 = time.time()
+    w = synth.make_tensor_config(cfg, args.shrink)
+    t_gen = time.time() - t0
+    t0 = time.time()
+    op = binding.Csf3Mttkrp(w.dims, w.i, w.j, w.k, w.vals, device=dev)
+    t_build = time.time() - t0
+    info = op.info
+    Bh, Ch = w.factors()
+    B, C = torch.from_numpy(Bh).to(dev), torch.from_numpy(Ch).to(dev)
+    A = torch.empty((w.dims[0], w.R), dtype=torch.float32, device=dev)
+    for _ in range(args.warmup):
+        op.mttkrp(B, C, A)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        op.mttkrp(B, C, A)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    R, nnz = w.R, w.nnz
+    # factorize-and-fuse operation count: 2 per entry and column for the fibre sums, 2 per fibre
+    # and column for the products with B (the paper's "Pairwise Contraction" count)
+    flops = 2.0 * nnz * R + 2.0 * info["fibers"] * R
+    gflops = flops / (ms_per_step * 1e-3) / 1e9
+    if args.calibrate_copy:
+        # plain device copies of known size (1 GiB read + 1 GiB written each), the yardstick of counter runs
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(args.calibrate_copy):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    binding.csf3_set_profiling(op.h, True)
+    runs = 1 if args.no_profile_pass else max(3, min(10, args.steps))
+    k_ms = r_ms = 0.0
+    for _ in range(runs):
+        op.mttkrp(B, C, A)
+        p = binding.csf3_get_profile(op.h)
+        k_ms += p["kernel_ms"] / runs
+        r_ms += p["reduce_ms"] / runs
+    binding.csf3_set_profiling(op.h, False)
+    row = 4 * R
+    # bytes the fibre kernel must move: entries, segment and item words, every referenced row of B
+    # and C once, every row of A or partial vector written once
+    alg = (8 * nnz + 8 * info["segments"] + 8 * info["items"] + row * (info["distinct_j"] + info["distinct_k"])
+           + row * info["items"])
+    achieved = alg / (k_ms * 1e-3) / 1e9 if k_ms > 0 else 0.0
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_mttkrp_kernel_{w.name}.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("hbm_bytes_per_launch")
+    roofline = {"bound": "hbm", "kernel": "mttkrp_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "avg_launch_ms": round(k_ms, 4), "launches_per_step": 1, "algorithmic_bytes_per_launch": int(alg)}
+    cpu_baseline = None
+    check = None
+    if not args.no_cpu_baseline:
+        import oracle
+        op.mttkrp(B, C, A)
+        torch.cuda.synchronize()
+        # calibrate on the first slices, then size the sample (a prefix of whole slices) to --cpu-seconds
+        cut = int(np.searchsorted(w.i, max(1, w.dims[0] // 256)))
+        t0 = time.perf_counter()
+        oracle.mttkrp(w.dims, w.i[:cut], w.j[:cut], w.k[:cut], w.vals[:cut], Bh, Ch)
+        t_cal = time.perf_counter() - t0
+        want = min(nnz, int(max(cut, 1) / max(t_cal, 1e-6) * args.cpu_seconds))
+        last = int(w.i[min(want, nnz) - 1]) if nnz else 0
+        cut = nnz if want >= nnz else int(np.searchsorted(w.i, last))          # whole slices only
+        rows_done = w.dims[0] if cut == nnz else last
+        t0 = time.perf_counter()
+        Aref, E = oracle.mttkrp(w.dims, w.i[:cut], w.j[:cut], w.k[:cut], w.vals[:cut], Bh, Ch)
+        t_cpu = time.perf_counter() - t0
+        fib = len(np.unique(w.i[:cut].astype(np.int64) * w.dims[1] + w.j[:cut]))
+        cpu_baseline = {"value": round((2.0 * cut * R + 2.0 * fib * R) / t_cpu / 1e9, 3), "unit": "GFLOP/s",
+                        "cores": oracle.num_threads(), "kind": "oracle",
+                        "sample": f"slices 0..{rows_done - 1} of the same tensor, all R={R} columns: {cut} nonzeros, "
+                                  f"{t_cpu:.1f} s (the oracle evaluates the unfactorized definition; the rate "
+                                  f"uses the same operation count as the GPU line)"}
+        got = A[:rows_done].cpu().numpy().astype(np.float64)
+        ratio = np.abs(got - Aref[:rows_done]) / np.maximum(E[:rows_done], 1e-300)
+        check = {"rows": int(rows_done), "max_err_over_bound": float(ratio.max()) if ratio.size else 0.0,
+                 "tolerance": 1e-5, "ok": bool(ratio.size == 0 or ratio.max() <= 1e-5)}
+    out = {
+        "metric": "fp32 order-3 MTTKRP GFLOP/s (2*nnz*R + 2*fibres*R), factorize-and-fuse over compressed sparse fibres",
+        "value": round(gflops, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "dims": list(w.dims), "nnz": nnz, "R": R, "fibers": info["fibers"],
+                   "items": info["items"], "op": "mttkrp"},
+        "roofline": roofline, "cpu_baseline": cpu_baseline,
+        "launch_ms": {"mttkrp_kernel": round(k_ms, 4), "reduce_kernel": round(r_ms, 4)},
+        "host_seconds": {"generate": round(t_gen, 1), "build_upload": round(t_build, 1)},
+        "check": check,
+        "paper": "single-thread and multi-node CPU results on FROSTT tensors only (section \"Performance Evaluation\"); not comparable",
+    }
+    print(json.dumps(out))
+    op.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -86,8 +190,9 @@ def main() -> int:
                          "n*k*4 written each) so that counter runs can be scaled")
     ap.add_argument("--no-profile-pass", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--kc", type=int, default=None)
-    ap.add_argument("--op", choices=("spmm", "sddmm"), default="spmm",
-                    help="spmm: Y = A.X (the headline); sddmm: S = A .* (U V^T) on the same layout")
+    ap.add_argument("--op", choices=("spmm", "sddmm", "mttkrp"), default="spmm",
+                    help="spmm: Y = A.X (the headline); sddmm: S = A .* (U V^T) on the same layout; "
+                         "mttkrp: order-3 MTTKRP on a synthetic tensor (--config 0 uniform, 1 skewed)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -101,6 +206,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
     dev = torch.device("cuda:0")
+    if args.op == "mttkrp":
+        return bench_mttkrp(args, torch, binding, synth, dev)
 
     t0 = time.time()
     w = synth.make_config(args.config, args.shrink)

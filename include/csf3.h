@@ -71,6 +71,15 @@ int csf3_mttkrp(csf3_handle *h, const float *B, const float *C, float *A, int32_
 
 int csf3_info(const csf3_handle *h, csf3_info_t *out);
 
+/*
+ * Profiling: when enabled, csf3_mttkrp brackets its two launches with HIP events on the caller's
+ * stream; csf3_get_profile waits for them and returns the times of the most recent product in
+ * milliseconds (the fibre kernel, and the reduction over the partial vectors of split slices).
+ * Errors: EINVAL, ENOTREADY (no profiled product has run), EHIP.
+ */
+int csf3_set_profiling(csf3_handle *h, int32_t enabled);
+int csf3_get_profile(csf3_handle *h, float *kernel_ms, float *reduce_ms);
+
 /* Thread-local text of the last error of a csf3_* call ("" if none). Never NULL. */
 const char *csf3_last_error(void);
 

@@ -28,7 +28,7 @@ EXPORTED = [
     "arrow_get_profile", "arrow_get_level_profile", "arrow_save", "arrow_load", "arrow_last_error",
     "arrow_destroy",
     "csf3_build", "csf3_device_bytes", "csf3_upload", "csf3_workspace_bytes", "csf3_set_workspace",
-    "csf3_mttkrp", "csf3_info", "csf3_last_error", "csf3_destroy",
+    "csf3_mttkrp", "csf3_info", "csf3_set_profiling", "csf3_get_profile", "csf3_last_error", "csf3_destroy",
 ]
 
 
@@ -140,6 +140,10 @@ def lib():
     L.csf3_mttkrp.argtypes = [vp, vp, vp, vp, i32, vp]
     L.csf3_info.restype = ctypes.c_int
     L.csf3_info.argtypes = [vp, ctypes.POINTER(csf3_info_t)]
+    L.csf3_set_profiling.restype = ctypes.c_int
+    L.csf3_set_profiling.argtypes = [vp, i32]
+    L.csf3_get_profile.restype = ctypes.c_int
+    L.csf3_get_profile.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
     L.csf3_last_error.restype = ctypes.c_char_p
     L.csf3_last_error.argtypes = []
     L.csf3_destroy.restype = None
@@ -423,6 +427,16 @@ def csf3_info(h: int) -> dict:
     out = csf3_info_t()
     _check3(lib().csf3_info(h, ctypes.byref(out)))
     return {f: getattr(out, f) for f, _ in out._fields_}
+
+
+def csf3_set_profiling(h: int, enabled: bool) -> None:
+    _check3(lib().csf3_set_profiling(h, 1 if enabled else 0))
+
+
+def csf3_get_profile(h: int) -> dict:
+    a, b = ctypes.c_float(), ctypes.c_float()
+    _check3(lib().csf3_get_profile(h, ctypes.byref(a), ctypes.byref(b)))
+    return {"kernel_ms": a.value, "reduce_ms": b.value}
 
 
 def csf3_destroy(h: int) -> None:

@@ -197,10 +197,11 @@ int launch_sddmm_chunks(const uint32_t* chunk_ptr, const uint32_t* chunk_mid, co
                         void* stream);
 
 // Order-3 MTTKRP over the compressed-sparse-fibre image (mttkrp.hip): one wavefront per item.
-// b_rows, c_rows = rows of the factor matrices (they decide whether 32-bit offsets are enough).
+// b_rows, c_rows = rows of the factor matrices (they decide whether 32-bit offsets are enough);
+// mean_segment = entries per segment on average (it picks how many row loads a round issues).
 int launch_mttkrp(const uint32_t* item_seg, const int32_t* item_dst, const uint32_t* seg_ptr,
                   const int32_t* seg_j, const Entry* entries, int64_t n_items, const float* B,
                   int64_t b_rows, const float* C, int64_t c_rows, float* A, float* partials, int32_t R,
-                  void* stream);
+                  double mean_segment, void* stream);
 
 }  // namespace arrow

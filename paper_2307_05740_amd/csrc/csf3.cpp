@@ -56,6 +56,8 @@ struct csf3_handle {
   unsigned char* dev = nullptr;
   unsigned char* ws = nullptr;
   size_t ws_bytes = 0;
+  bool profiling = false, profiled = false;
+  hipEvent_t ev[3] = {nullptr, nullptr, nullptr};   // before the kernel, between, after the reduction
 };
 
 extern "C" {
@@ -234,17 +236,43 @@ int csf3_mttkrp(csf3_handle* h, const float* B, const float* C, float* A, int32_
   if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C) % 16) return fail3(ARROW_EINVAL, "A, B and C must be 16-byte aligned");
   float* partials = reinterpret_cast<float*>(h->ws);
   auto at = [&](size_t off) { return h->dev + off; };
+  const bool prof = h->profiling && h->ev[0];
+  if (prof) (void)hipEventRecord(h->ev[0], (hipStream_t)stream);
   int rc = arrow::launch_mttkrp(reinterpret_cast<const uint32_t*>(at(h->off_item_seg)),
                                 reinterpret_cast<const int32_t*>(at(h->off_item_dst)),
                                 reinterpret_cast<const uint32_t*>(at(h->off_seg_ptr)),
                                 reinterpret_cast<const int32_t*>(at(h->off_seg_j)),
                                 reinterpret_cast<const arrow::Entry*>(at(h->off_entries)), h->n_items, B,
-                                h->J, C, h->K, A, partials, R, stream);
+                                h->J, C, h->K, A, partials, R,
+                                h->n_seg ? (double)h->nnz / (double)h->n_seg : 0.0, stream);
   if (rc) return fail3(ARROW_EHIP, "mttkrp kernel launch: %s", hipGetErrorString((hipError_t)rc));
+  if (prof) (void)hipEventRecord(h->ev[1], (hipStream_t)stream);
   rc = arrow::launch_reduce(reinterpret_cast<const uint32_t*>(at(h->off_split_ptr)),
                             reinterpret_cast<const int32_t*>(at(h->off_split_y)), h->n_split, partials, A, R,
                             false, stream);
   if (rc) return fail3(ARROW_EHIP, "reduce kernel launch: %s", hipGetErrorString((hipError_t)rc));
+  if (prof) { (void)hipEventRecord(h->ev[2], (hipStream_t)stream); h->profiled = true; }
+  return ARROW_OK;
+}
+
+int csf3_set_profiling(csf3_handle* h, int32_t enabled) {
+  if (!h) return fail3(ARROW_EINVAL, "handle is NULL");
+  if (enabled && !h->ev[0]) {
+    for (hipEvent_t& e : h->ev)
+      if (hipEventCreate(&e) != hipSuccess) { e = nullptr; return fail3(ARROW_EHIP, "event creation failed"); }
+  }
+  h->profiling = enabled != 0;
+  h->profiled = false;
+  return ARROW_OK;
+}
+
+int csf3_get_profile(csf3_handle* h, float* kernel_ms, float* reduce_ms) {
+  if (!h || !kernel_ms || !reduce_ms) return fail3(ARROW_EINVAL, "NULL argument");
+  if (!h->profiled) return fail3(ARROW_ENOTREADY, "no profiled product has run");
+  hipError_t e = hipEventSynchronize(h->ev[2]);
+  if (e == hipSuccess) e = hipEventElapsedTime(kernel_ms, h->ev[0], h->ev[1]);
+  if (e == hipSuccess) e = hipEventElapsedTime(reduce_ms, h->ev[1], h->ev[2]);
+  if (e != hipSuccess) return fail3(ARROW_EHIP, "event timing: %s", hipGetErrorString(e));
   return ARROW_OK;
 }
 
@@ -258,6 +286,11 @@ int csf3_info(const csf3_handle* h, csf3_info_t* out) {
   return ARROW_OK;
 }
 
-void csf3_destroy(csf3_handle* h) { delete h; }
+void csf3_destroy(csf3_handle* h) {
+  if (!h) return;
+  for (hipEvent_t e : h->ev)
+    if (e) (void)hipEventDestroy(e);
+  delete h;
+}
 
 }  // extern "C"

@@ -63,7 +63,8 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
 #pragma unroll
       for (int u = 0; u < U; ++u) e[u] = ent[p + u < hi ? p + u : hi - 1];   // one request per lane group
 #pragma unroll
-      for (int u = 0; u < U; ++u) cr[u] = load_row<VEC, SMALL_C>(Cb, e[u].xrow, row_bytes, col_bytes);
+      for (int u = 0; u < U; ++u)
+        cr[u] = p + u < hi ? load_row<VEC, SMALL_C>(Cb, e[u].xrow, row_bytes, col_bytes) : vzero<VEC>();
 #pragma unroll
       for (int u = 0; u < U; ++u) vfma(x, p + u < hi ? e[u].val : 0.f, cr[u]);
     }
@@ -83,8 +84,10 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
 int launch_mttkrp(const uint32_t* item_seg, const int32_t* item_dst, const uint32_t* seg_ptr,
                   const int32_t* seg_j, const Entry* entries, int64_t n_items, const float* B,
                   int64_t b_rows, const float* C, int64_t c_rows, float* A, float* partials, int32_t R,
-                  void* stream) {
+                  double mean_segment, void* stream) {
   if (n_items <= 0) return 0;
+  // row loads issued per round of a segment: more than the segments hold only adds predicated slots
+  const int rounds = mean_segment < 2.5 ? 2 : (mean_segment < 6.0 ? 4 : 8);
   const Shape s = pick_shape(R, 0);
   const bool small_b = small_matrix(b_rows, R), small_c = small_matrix(c_rows, R);
   return dispatch_shape(s, [&](auto Vc, auto L) -> int {
@@ -92,11 +95,14 @@ int launch_mttkrp(const uint32_t* item_seg, const int32_t* item_dst, const uint3
     const int64_t blocks = ceil_div(n_items, kBlock / 64);
     if (blocks > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
     dim3 grid((unsigned)blocks, (unsigned)s.slices);
-#define ARROW_LAUNCH(SB, SC)                                                                        \
-  hipLaunchKernelGGL((mttkrp_kernel<VEC, LPR, 8, SB, SC>), grid, dim3(kBlock), 0, (hipStream_t)stream, \
+#define ARROW_LAUNCH(UU, SM)                                                                        \
+  hipLaunchKernelGGL((mttkrp_kernel<VEC, LPR, UU, SM, SM>), grid, dim3(kBlock), 0, (hipStream_t)stream, \
                      item_seg, item_dst, seg_ptr, seg_j, entries, n_items, B, C, A, partials, (int)R)
-    if (small_b && small_c) ARROW_LAUNCH(true, true);
-    else ARROW_LAUNCH(false, false);
+    if (small_b && small_c) {
+      if (rounds == 2) ARROW_LAUNCH(2, true); else if (rounds == 4) ARROW_LAUNCH(4, true); else ARROW_LAUNCH(8, true);
+    } else {
+      if (rounds == 2) ARROW_LAUNCH(2, false); else if (rounds == 4) ARROW_LAUNCH(4, false); else ARROW_LAUNCH(8, false);
+    }
 #undef ARROW_LAUNCH
     return (int)hipGetLastError();
   });

@@ -128,3 +128,22 @@ def test_config4_chung_lu_16m_fifth_power_sampled(torch):
     for s in range(0, w.n, 1 << 21):
         check(got[s:s + (1 << 21)], Xl[s:s + (1 << 21)], El[s:s + (1 << 21)], scale=w.l)
     op.close()
+
+
+@pytest.mark.parametrize("idx", [0, 1])
+def test_mttkrp_tensor_workloads_full(torch, idx):
+    """Order-3 MTTKRP at the sizes ``bench.py --op mttkrp`` times: the uniform 4096^3 tensor at
+    density 0.1 % and the skewed 2^20 x 2^17 x 2^17 tensor, R = 64; the whole result is compared."""
+    print(f"generating tensor workload {idx} ...", flush=True)
+    w = synth.make_tensor_config(idx)
+    B, C = w.factors()
+    print(f"building nnz={w.nnz} ...", flush=True)
+    op = binding.Csf3Mttkrp(w.dims, w.i, w.j, w.k, w.vals)
+    Ad = torch.full((w.dims[0], w.R), float("nan"), dtype=torch.float32, device="cuda")
+    op.mttkrp(torch.from_numpy(B).cuda(), torch.from_numpy(C).cuda(), Ad)
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(Ad).any())
+    print("oracle ...", flush=True)
+    Aref, E = oracle.mttkrp(w.dims, w.i, w.j, w.k, w.vals, B, C)
+    check(Ad.cpu().numpy(), Aref, E)
+    op.close()
