@@ -217,7 +217,7 @@ int arrow_self_check(const arrow_handle *h);
  * ARROW_WINDOW_SHARE_X1000 (the tiles of a level are kept when they hold at least this / 1000 of
  * the level's entries, default 50),
  * ARROW_PANEL (1: head rows of level 0 with few entries per column window run their head-block
- * entries in panels: 256 rows per group, one workgroup per group and column class with the
+ * entries in panels: 128 rows per group, one workgroup per group and column class with the
  * group's accumulators in LDS, class c served by accelerator die c; default 0), ARROW_PANEL_MIN
  * (fewest head-block entries of a row that joins a panel, default 8),
  * ARROW_SEPARATORS and ARROW_BFS_TAIL (0 disables the separator rule / the breadth-first

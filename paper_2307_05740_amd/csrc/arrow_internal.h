@@ -51,7 +51,7 @@ constexpr int kItemsPerGroupBlock = 64;  // group-list items per workgroup of th
 // class (staged head row mod kDies) to kDies workgroups, one per accelerator die, each keeping the
 // group's accumulators in LDS and streaming its entries in kPanelBins lane-group streams
 constexpr int kPanelBins = 32;
-constexpr int kPanelRows = 256;
+constexpr int kPanelRows = 128;
 constexpr int kPanelClassShift = 6;       // staged head rows are dealt to the column classes 64 at a time
 inline int panel_class(uint32_t staged_row) { return (int)((staged_row >> kPanelClassShift) & (kDies - 1)); }
 constexpr int kPanelRowShift = 24;       // panel entry code = (row inside the workgroup << 24) | staged head row

@@ -842,12 +842,12 @@ int launch_sddmm_chunks(const uint32_t* chunk_ptr, const uint32_t* chunk_mid, co
 }
 
 namespace {
-// (VEC, LPR) with at most 16 lanes per row: the panel kernel runs kPanelBins lane groups per workgroup
+// (VEC, LPR) with at most 32 lanes per row: the panel kernel runs kPanelBins lane groups per workgroup
 template <typename F>
 int dispatch_narrow(const Shape& s, F&& f) {
 #define ARROW_CASE(V, L) \
   if (s.vec == V && s.lpr == L) return f(std::integral_constant<int, V>{}, std::integral_constant<int, L>{});
-#define ARROW_CASES(V) ARROW_CASE(V, 1) ARROW_CASE(V, 2) ARROW_CASE(V, 4) ARROW_CASE(V, 8) ARROW_CASE(V, 16)
+#define ARROW_CASES(V) ARROW_CASE(V, 1) ARROW_CASE(V, 2) ARROW_CASE(V, 4) ARROW_CASE(V, 8) ARROW_CASE(V, 16) ARROW_CASE(V, 32)
   ARROW_CASES(4)
   ARROW_CASES(2)
   ARROW_CASES(1)
@@ -861,7 +861,7 @@ int launch_panel(const uint32_t* panel_ptr, const int32_t* panel_y, const Entry*
                  int64_t n_groups, const float* Xh, int64_t xh_rows, float* part, int32_t k, void* stream) {
   if (n_groups <= 0) return 0;
   const int vec = (k % 4 == 0) ? 4 : (k % 2 == 0) ? 2 : 1;
-  const Shape s = pick_shape(k, 16 * vec);         // at most 16 lanes per row: LDS rows of at most 64 floats
+  const Shape s = pick_shape(k, 32 * vec);         // at most 32 lanes per row: LDS rows of at most 128 floats
   const bool small = small_matrix(xh_rows, k);
   return dispatch_narrow(s, [&](auto Vc, auto L) -> int {
     constexpr int VEC = decltype(Vc)::value, LPR = decltype(L)::value;
