@@ -23,14 +23,19 @@
 //     lands on the same die as well.  classes / 8 phases follow each other; inside a
 //     (phase, die) queue items are ordered by the column window they start in; queues are
 //     padded with empty slots to equal length.
-//   * Rows not split by class keep whole-row chunks cut at column-window boundaries
-//     (windows are merged until a chunk holds chunk_min entries) and ordered by window, so
-//     that the wavefronts in flight read one neighbourhood of X rows; they form the last phase.
+//   * Rows not split by class are cut at column-window boundaries (windows are merged until a
+//     piece holds chunk_min entries); a piece of at most piece_max entries is a group-list item,
+//     a longer one is cut into wave-list chunks of at most chunk_nnz entries.  Both lists are
+//     ordered by the window an item starts in, so that the wavefronts in flight read one
+//     neighbourhood of X rows; these items form the last phase of their list.
 //   * Head staging.  The head rows of P_i X are gathered once per product into a contiguous
 //     buffer, class by class, so a die's slice is one contiguous range.  Entries of head
 //     columns of long rows carry the row of that buffer; they come first in every item
 //     (entries are ordered by column position) and the item's `mid` marks where they end.
 //     All other entries carry perm[q]: the permutation gather stays fused.
+//   * Head panels (optional, off by default): see the planning code below.
+// Besides the image the packer builds the entry map (image order -> index of the entry in the
+// caller's CSR arrays), which the sampled dense-dense product needs for its output.
 #include "arrow_internal.h"
 
 #include <omp.h>
@@ -225,7 +230,7 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
     // workgroups, and workgroup (group, class) has the linear id group * 8 + class, so class c is
     // always served by accelerator die c: a die's L2 only ever holds an eighth of the staged head
     // X_0.  Each workgroup keeps the group's accumulators in LDS and streams its entries in
-    // kPanelBins lane-group streams of equal length, each ordered by column window, then row; a row's
+    // kPanelBins lane-group streams of equal length, each ordered by row, then column; a row's
     // class entries all sit in one stream, so no two lane groups touch the same accumulator.
     // The eight class results of a row are added to Y afterwards, in class order.
     // What is left of such a row (columns outside the head) is planned like any other row.
