@@ -148,6 +148,9 @@ int arrow_set_workspace(arrow_handle *h, void *dev_ws, size_t bytes);
  * Level 0 stores every row of Y (perm_0 is a full permutation); later levels
  * add into the rows they touch, in stream order, so the result does not
  * depend on scheduling (no floating-point atomics are used).
+ * With profiling off the call only launches kernels on `stream` (no allocation, no memset, no
+ * synchronisation), so it may be recorded into a HIP graph by a caller that captures `stream`;
+ * the same holds for arrow_spmm_iter (plus one device-to-device copy for odd l) and arrow_sddmm.
  * Errors: EINVAL (NULL, k < 1, X == Y), ENOTREADY, ETOOSMALL (workspace bound
  * for a smaller k), EHIP.
  */

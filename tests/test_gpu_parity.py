@@ -386,3 +386,38 @@ def test_exported_levels_match_what_the_gpu_ran(torch):
     Yref, B = oracle.spmm(*csr_of(w), X)
     assert_within(Y, Yref, B)
     op.close()
+
+
+def test_product_under_graph_capture(torch):
+    """The product only launches kernels on the caller's stream (no allocation, no memset), so a
+    caller can capture it into a HIP graph; every replay is checked against the eager result, with
+    eager work and synchronisation between the replays."""
+    w = synth.make_config(0)
+    op = binding.ArrowSpMM(*csr_of(w), w.b)
+    Xs = [synth.normal_matrix(w.n, 24, seed=900 + t) for t in range(3)]
+    Xd = torch.from_numpy(Xs[0]).cuda()
+    Yd = torch.empty_like(Xd)
+    Zd = Xd.clone()
+    op.spmm(Xd, Yd)                                     # eager first: sizes the workspace
+    op.spmm_iter(Zd, 3)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        op.spmm(Xd, Yd)                                 # Y = A X
+        Zd.copy_(Xd)
+        op.spmm_iter(Zd, 3)                             # Z = A^3 X (odd count: ends with a device copy)
+    for t in range(3):
+        Xd.copy_(torch.from_numpy(Xs[t]).cuda())
+        g.replay()
+        torch.cuda.synchronize()
+        Yg, Zg = Yd.cpu().numpy(), Zd.cpu().numpy()
+        Xe = torch.from_numpy(Xs[t]).cuda()
+        Ye = op.spmm(Xe).cpu().numpy()                  # eager work between the replays
+        Ze = Xe.clone()
+        op.spmm_iter(Ze, 3)
+        torch.cuda.synchronize()
+        assert np.array_equal(Yg.view(np.uint32), Ye.view(np.uint32)), t
+        assert np.array_equal(Zg.view(np.uint32), Ze.cpu().numpy().view(np.uint32)), t
+        Yref, B = oracle.spmm(*csr_of(w), Xs[t])
+        assert_within(Yg, Yref, B)
+    op.close()
