@@ -54,6 +54,24 @@ __device__ __forceinline__ void vstore(float* p, typename Vec<VEC>::type v) {
   *reinterpret_cast<typename Vec<VEC>::type*>(p) = v;
 }
 
+// Store of a result row that this product does not read again: the non-temporal hint keeps the
+// 4 k bytes per output row from displacing rows of X in the L2 (measured on the R-MAT workload:
+// rows kernel 3.97 -> 3.71 ms, reduction 0.38 -> 0.33 ms; the same hint on loads of X rows or of
+// the entry stream made the product slower).
+typedef float stream_v2f __attribute__((ext_vector_type(2)));
+typedef float stream_v4f __attribute__((ext_vector_type(4)));
+template <int VEC>
+__device__ __forceinline__ void vstore_stream(float* p, typename Vec<VEC>::type v);
+template <> __device__ __forceinline__ void vstore_stream<1>(float* p, float v) { __builtin_nontemporal_store(v, p); }
+template <> __device__ __forceinline__ void vstore_stream<2>(float* p, float2 v) {
+  stream_v2f t; t.x = v.x; t.y = v.y;
+  __builtin_nontemporal_store(t, reinterpret_cast<stream_v2f*>(p));
+}
+template <> __device__ __forceinline__ void vstore_stream<4>(float* p, float4 v) {
+  stream_v4f t; t.x = v.x; t.y = v.y; t.z = v.z; t.w = v.w;
+  __builtin_nontemporal_store(t, reinterpret_cast<stream_v4f*>(p));
+}
+
 // Load VEC columns of row `row` of a row-major matrix.  `base` is wavefront-uniform,
 // col_bytes the lane's byte offset inside a row, row_bytes = 4 k.
 // SMALL: the matrix has at most 2^24 rows and 2^32 bytes, so the byte offset is one 24-bit

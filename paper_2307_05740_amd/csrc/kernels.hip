@@ -109,7 +109,7 @@ __global__ __launch_bounds__(kBlock) void rows_kernel(
       if (dst >= 0) {
         float* y = Y + (size_t)dst * (size_t)k + c;
         if (accumulate) vadd(acc, vload<VEC>(y));
-        vstore<VEC>(y, acc);
+        vstore_stream<VEC>(y, acc);
       } else {
         vstore<VEC>(partials + (size_t)(-1 - dst) * (size_t)k + c, acc);
       }
@@ -193,7 +193,7 @@ __global__ __launch_bounds__(kBlock) void chunks_kernel(
     if (dst >= 0) {
       float* y = Y + (size_t)dst * (size_t)k + c;
       if (accumulate) vadd(acc, vload<VEC>(y));
-      vstore<VEC>(y, acc);
+      vstore_stream<VEC>(y, acc);
     } else {
       vstore<VEC>(partials + (size_t)(-1 - dst) * (size_t)k + c, acc);
     }
@@ -269,7 +269,7 @@ __global__ __launch_bounds__(kWinBlock) void window_kernel(
     if (col_ok) {
       float* y = Y + (size_t)wrow_y[wr] * (size_t)k + c;
       if (accumulate) vadd(acc, vload<VEC>(y));
-      vstore<VEC>(y, acc);
+      vstore_stream<VEC>(y, acc);
     }
   }
 }
@@ -581,7 +581,7 @@ __global__ __launch_bounds__(kBlock) void panel_combine_kernel(
   for (int x = 1; x < kDies; ++x) vadd(acc, p[x]);
   float* yp = Y + (size_t)y * (size_t)k + c;
   vadd(acc, vload<VEC>(yp));
-  vstore<VEC>(yp, acc);
+  vstore_stream<VEC>(yp, acc);
 }
 
 // Sampled product over the panel entries: lane group per bin, NB entries at a time; the row
@@ -666,7 +666,7 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(
   if (g == 0 && col_ok) {
     float* y = Y + (size_t)split_y[row] * (size_t)k + c;
     if (accumulate) vadd(acc, vload<VEC>(y));
-    vstore<VEC>(y, acc);
+    vstore_stream<VEC>(y, acc);
   }
 }
 
