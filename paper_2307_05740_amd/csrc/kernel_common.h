@@ -72,6 +72,18 @@ template <> __device__ __forceinline__ void vstore_stream<4>(float* p, float4 v)
   __builtin_nontemporal_store(t, reinterpret_cast<stream_v4f*>(p));
 }
 
+// Load of a row that is read exactly once (a partial vector in the reduction, the old value of a
+// Y row a later level adds to), same hint.
+template <int VEC>
+__device__ __forceinline__ typename Vec<VEC>::type vload_stream(const float* p);
+template <> __device__ __forceinline__ float vload_stream<1>(const float* p) { return __builtin_nontemporal_load(p); }
+template <> __device__ __forceinline__ float2 vload_stream<2>(const float* p) {
+  stream_v2f t = __builtin_nontemporal_load(reinterpret_cast<const stream_v2f*>(p)); return make_float2(t.x, t.y);
+}
+template <> __device__ __forceinline__ float4 vload_stream<4>(const float* p) {
+  stream_v4f t = __builtin_nontemporal_load(reinterpret_cast<const stream_v4f*>(p)); return make_float4(t.x, t.y, t.z, t.w);
+}
+
 // Load VEC columns of row `row` of a row-major matrix.  `base` is wavefront-uniform,
 // col_bytes the lane's byte offset inside a row, row_bytes = 4 k.
 // SMALL: the matrix has at most 2^24 rows and 2^32 bytes, so the byte offset is one 24-bit

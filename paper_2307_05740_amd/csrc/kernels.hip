@@ -108,10 +108,10 @@ __global__ __launch_bounds__(kBlock) void rows_kernel(
     if (col_ok) {
       if (dst >= 0) {
         float* y = Y + (size_t)dst * (size_t)k + c;
-        if (accumulate) vadd(acc, vload<VEC>(y));
+        if (accumulate) vadd(acc, vload_stream<VEC>(y));
         vstore_stream<VEC>(y, acc);
       } else {
-        vstore<VEC>(partials + (size_t)(-1 - dst) * (size_t)k + c, acc);
+        vstore_stream<VEC>(partials + (size_t)(-1 - dst) * (size_t)k + c, acc);
       }
     }
   }
@@ -192,10 +192,10 @@ __global__ __launch_bounds__(kBlock) void chunks_kernel(
     const int32_t dst = chunk_dst[ch];
     if (dst >= 0) {
       float* y = Y + (size_t)dst * (size_t)k + c;
-      if (accumulate) vadd(acc, vload<VEC>(y));
+      if (accumulate) vadd(acc, vload_stream<VEC>(y));
       vstore_stream<VEC>(y, acc);
     } else {
-      vstore<VEC>(partials + (size_t)(-1 - dst) * (size_t)k + c, acc);
+      vstore_stream<VEC>(partials + (size_t)(-1 - dst) * (size_t)k + c, acc);
     }
   }
 }
@@ -268,7 +268,7 @@ __global__ __launch_bounds__(kWinBlock) void window_kernel(
     }
     if (col_ok) {
       float* y = Y + (size_t)wrow_y[wr] * (size_t)k + c;
-      if (accumulate) vadd(acc, vload<VEC>(y));
+      if (accumulate) vadd(acc, vload_stream<VEC>(y));
       vstore_stream<VEC>(y, acc);
     }
   }
@@ -654,18 +654,18 @@ __global__ __launch_bounds__(kBlock) void reduce_kernel(
   V acc = vzero<VEC>();
   uint32_t s = lo + g;
   for (; s + 3 * G < hi; s += 4 * G) {
-    V p0 = vload<VEC>(Pc + (size_t)s * (size_t)k);
-    V p1 = vload<VEC>(Pc + (size_t)(s + G) * (size_t)k);
-    V p2 = vload<VEC>(Pc + (size_t)(s + 2 * G) * (size_t)k);
-    V p3 = vload<VEC>(Pc + (size_t)(s + 3 * G) * (size_t)k);
+    V p0 = vload_stream<VEC>(Pc + (size_t)s * (size_t)k);
+    V p1 = vload_stream<VEC>(Pc + (size_t)(s + G) * (size_t)k);
+    V p2 = vload_stream<VEC>(Pc + (size_t)(s + 2 * G) * (size_t)k);
+    V p3 = vload_stream<VEC>(Pc + (size_t)(s + 3 * G) * (size_t)k);
     vadd(acc, p0); vadd(acc, p1); vadd(acc, p2); vadd(acc, p3);
   }
-  for (; s < hi; s += G) vadd(acc, vload<VEC>(Pc + (size_t)s * (size_t)k));
+  for (; s < hi; s += G) vadd(acc, vload_stream<VEC>(Pc + (size_t)s * (size_t)k));
 #pragma unroll
   for (int m = LPR; m < 64; m <<= 1) vadd(acc, vshfl_xor(acc, m));
   if (g == 0 && col_ok) {
     float* y = Y + (size_t)split_y[row] * (size_t)k + c;
-    if (accumulate) vadd(acc, vload<VEC>(y));
+    if (accumulate) vadd(acc, vload_stream<VEC>(y));
     vstore_stream<VEC>(y, acc);
   }
 }
