@@ -199,7 +199,14 @@ int launch_sddmm_chunks(const uint32_t* chunk_ptr, const uint32_t* chunk_mid, co
 // Order-3 MTTKRP over the compressed-sparse-fibre image (mttkrp.hip): one wavefront per item.
 // b_rows, c_rows = rows of the factor matrices (they decide whether 32-bit offsets are enough);
 // mean_segment = entries per segment on average (it picks how many row loads a round issues).
-int launch_mttkrp(const uint32_t* item_seg, const int32_t* item_dst, const uint32_t* seg_ptr,
+// Limits of one work item of the fibre image: the wavefront that owns the item stages its entries
+// and segment descriptors in LDS, so both are bounded.
+constexpr int kCsfSegMax = 64;      // most entries of a segment
+constexpr int kCsfItemNnz = 512;    // most entries of an item
+constexpr int kCsfItemSegs = 128;   // most segments of an item
+// item_ent[it] = index of the item's first entry (the items' entries are consecutive).
+int launch_mttkrp(const uint32_t* item_seg, const uint32_t* item_ent, const int32_t* item_dst,
+                  const uint32_t* seg_ptr,
                   const int32_t* seg_j, const Entry* entries, int64_t n_items, const float* B,
                   int64_t b_rows, const float* C, int64_t c_rows, float* A, float* partials, int32_t R,
                   double mean_segment, void* stream);

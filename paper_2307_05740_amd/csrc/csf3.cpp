@@ -5,7 +5,7 @@
 // Image: the entries sorted by (i, j, k) as {k, value} pairs; SEGMENTS, runs of at most
 // kSegMax entries of one fibre (i, j) with the fibre's j (a long fibre is cut: the product with
 // B(j, :) distributes over the pieces); ITEMS, runs of consecutive segments of one slice i with at
-// most kItemNnz entries, one per wavefront, with a destination: row i of A when the slice is one
+// most kItemNnz entries and kItemSegs segments, one per wavefront, with a destination: row i of A when the slice is one
 // item, else a partial-vector slot that the reduction pass sums in a fixed order.  Every i in
 // [0, I) has at least one item (an empty one stores zeros), so A is fully overwritten.
 #include <hip/hip_runtime.h>
@@ -40,8 +40,9 @@ int fail3(int code, const char* fmt, ...) {
 
 constexpr size_t kAlign3 = 256;
 size_t align3(size_t x) { return (x + kAlign3 - 1) / kAlign3 * kAlign3; }
-constexpr int64_t kSegMax = 64;     // most entries of a segment
-constexpr int64_t kItemNnz = 512;   // an item is closed once it holds this many entries
+constexpr int64_t kSegMax = arrow::kCsfSegMax;      // most entries of a segment
+constexpr int64_t kItemNnz = arrow::kCsfItemNnz;    // an item is closed before it would hold more entries
+constexpr int64_t kItemSegs = arrow::kCsfItemSegs;  // ... or more segments than this
 
 }  // namespace
 
@@ -51,7 +52,7 @@ struct csf3_handle {
   int64_t distinct_j = 0, distinct_k = 0;
   double build_seconds = 0.0;
   std::vector<unsigned char> bytes;   // packed host copy of the image
-  size_t off_seg_ptr = 0, off_seg_j = 0, off_item_seg = 0, off_item_dst = 0, off_split_ptr = 0,
+  size_t off_seg_ptr = 0, off_seg_j = 0, off_item_seg = 0, off_item_dst = 0, off_item_ent = 0, off_split_ptr = 0,
          off_split_y = 0, off_entries = 0;
   unsigned char* dev = nullptr;
   unsigned char* ws = nullptr;
@@ -125,6 +126,7 @@ int csf3_build(int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* ti, 
     seg_ptr.push_back((uint32_t)nnz);
     h->n_seg = (int64_t)seg_j.size();
     // items: per slice i (empty slices included), consecutive segments up to kItemNnz entries
+    // and kItemSegs segments
     std::vector<uint32_t> item_seg, split_ptr;
     std::vector<int32_t> item_dst, split_y;
     split_ptr.push_back(0);
@@ -139,9 +141,11 @@ int csf3_build(int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* ti, 
       while (s < h->n_seg && seg_i[s] == i) {
         item_seg.push_back((uint32_t)s);
         item_dst.push_back((int32_t)i);
-        int64_t cnt = 0;
-        while (s < h->n_seg && seg_i[s] == i && (cnt == 0 || cnt + (seg_ptr[s + 1] - seg_ptr[s]) <= kItemNnz)) {
+        int64_t cnt = 0, segs = 0;
+        while (s < h->n_seg && seg_i[s] == i && segs < kItemSegs &&
+               (cnt == 0 || cnt + (seg_ptr[s + 1] - seg_ptr[s]) <= kItemNnz)) {
           cnt += seg_ptr[s + 1] - seg_ptr[s];
+          ++segs;
           ++s;
         }
       }
@@ -169,6 +173,7 @@ int csf3_build(int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* ti, 
     h->off_seg_j = total;     total = align3(total + sizeof(int32_t) * seg_j.size());
     h->off_item_seg = total;  total = align3(total + sizeof(uint32_t) * item_seg.size());
     h->off_item_dst = total;  total = align3(total + sizeof(int32_t) * item_dst.size());
+    h->off_item_ent = total;  total = align3(total + sizeof(uint32_t) * item_seg.size());
     h->off_split_ptr = total; total = align3(total + sizeof(uint32_t) * split_ptr.size());
     h->off_split_y = total;   total = align3(total + sizeof(int32_t) * split_y.size());
     h->off_entries = total;   total = align3(total + sizeof(arrow::Entry) * (size_t)nnz);
@@ -178,6 +183,10 @@ int csf3_build(int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* ti, 
     if (!seg_j.empty()) std::memcpy(base + h->off_seg_j, seg_j.data(), sizeof(int32_t) * seg_j.size());
     std::memcpy(base + h->off_item_seg, item_seg.data(), sizeof(uint32_t) * item_seg.size());
     std::memcpy(base + h->off_item_dst, item_dst.data(), sizeof(int32_t) * item_dst.size());
+    {
+      uint32_t* item_ent = reinterpret_cast<uint32_t*>(base + h->off_item_ent);
+      for (size_t t = 0; t < item_seg.size(); ++t) item_ent[t] = seg_ptr[item_seg[t]];
+    }
     std::memcpy(base + h->off_split_ptr, split_ptr.data(), sizeof(uint32_t) * split_ptr.size());
     if (!split_y.empty()) std::memcpy(base + h->off_split_y, split_y.data(), sizeof(int32_t) * split_y.size());
     arrow::Entry* ent = reinterpret_cast<arrow::Entry*>(base + h->off_entries);
@@ -239,6 +248,7 @@ int csf3_mttkrp(csf3_handle* h, const float* B, const float* C, float* A, int32_
   const bool prof = h->profiling && h->ev[0];
   if (prof) (void)hipEventRecord(h->ev[0], (hipStream_t)stream);
   int rc = arrow::launch_mttkrp(reinterpret_cast<const uint32_t*>(at(h->off_item_seg)),
+                                reinterpret_cast<const uint32_t*>(at(h->off_item_ent)),
                                 reinterpret_cast<const int32_t*>(at(h->off_item_dst)),
                                 reinterpret_cast<const uint32_t*>(at(h->off_seg_ptr)),
                                 reinterpret_cast<const int32_t*>(at(h->off_seg_j)),
