@@ -49,6 +49,12 @@ namespace {
 // its lane groups take them round-robin.  Entries [lo, mid) of an item read rows of the staged
 // head buffer Xh, entries [mid, hi) read rows of X.
 // ---------------------------------------------------------------------------
+// The workgroup first copies the descriptors of its items and, when they fit the staging buffer
+// (they always do for the short rows), all their entries -- one contiguous range -- into LDS with
+// coalesced loads; after that the only memory latency a lane group waits for is that of the rows
+// it gathers.  A workgroup whose entries do not fit streams them per item through a strip.
+constexpr int kRowsStage = 1024;   // entries a workgroup stages at once (8 KiB)
+
 template <int VEC, int LPR, int U, bool SMALL>
 __global__ __launch_bounds__(kBlock) void rows_kernel(
     const uint32_t* __restrict__ rows_ptr, const uint32_t* __restrict__ rows_mid,
@@ -60,42 +66,50 @@ __global__ __launch_bounds__(kBlock) void rows_kernel(
   // entries a lane group parks in LDS per batch: four loads per lane, between 8 and 64 entries
   constexpr int SG = 4 * LPR < 8 ? 8 : (4 * LPR > 64 ? 64 : 4 * LPR);
   constexpr int UU = U < SG ? U : SG;
-  __shared__ Entry strip[GPB * SG];
+  constexpr int NST = GPB * SG > kRowsStage ? GPB * SG : kRowsStage;   // the buffer doubles as the per-group strips
+  __shared__ Entry stage[NST];
+  __shared__ uint32_t s_ptr[kItemsPerGroupBlock + 1];
+  __shared__ uint32_t s_mid[kItemsPerGroupBlock];
+  __shared__ int32_t s_dst[kItemsPerGroupBlock];
   const int tid = threadIdx.x;
   const int l = tid % LPR;
   const int c = l * VEC + blockIdx.y * (LPR * VEC);
   const bool col_ok = c < k;
   const uint32_t row_bytes = 4u * (uint32_t)k;
   const uint32_t col_bytes = col_ok ? 4u * (uint32_t)c : 0u;   // lanes past the last column read column 0
-  Entry* grp = strip + (tid / LPR) * SG;        // the group's SG slots
   const int64_t first = (int64_t)blockIdx.x * kItemsPerGroupBlock;
-  for (int it = tid / LPR; it < kItemsPerGroupBlock; it += GPB) {
-    const int64_t r = first + it;
-    if (r >= n_rows) break;
-    const int32_t dst = rows_dst[r];
+  const int n_it = n_rows - first < kItemsPerGroupBlock ? (int)(n_rows - first) : kItemsPerGroupBlock;
+  if (n_it <= 0) return;
+  if (tid <= n_it) s_ptr[tid] = rows_ptr[first + tid];
+  if (tid < n_it) { s_mid[tid] = rows_mid[first + tid]; s_dst[tid] = rows_dst[first + tid]; }
+  __syncthreads();
+  const uint32_t e0 = s_ptr[0];
+  const uint32_t total = s_ptr[n_it] - e0;
+  const bool staged = total <= (uint32_t)NST;
+  if (staged) {
+    for (uint32_t t = tid; t < total; t += kBlock) stage[t] = ent[e0 + t];
+    __syncthreads();
+  }
+  Entry* grp = stage + (tid / LPR) * SG;        // the group's SG slots when the entries are streamed
+  for (int it = tid / LPR; it < n_it; it += GPB) {
+    const int32_t dst = s_dst[it];
     if (dst == INT32_MIN) continue;             // padding slot of the die queues
-    const uint32_t lo = rows_ptr[r];
-    const uint32_t mid = rows_mid[r];
-    const uint32_t hi = rows_ptr[r + 1];
+    const uint32_t lo = s_ptr[it];
+    const uint32_t mid = s_mid[it];
+    const uint32_t hi = s_ptr[it + 1];
     V acc = vzero<VEC>();
-    for (uint32_t b0 = lo; b0 < hi; b0 += SG) {
-      const uint32_t nb = hi - b0 < (uint32_t)SG ? hi - b0 : (uint32_t)SG;
-#pragma unroll
-      for (int t = 0; t < SG / LPR; ++t) {
-        const uint32_t idx = (uint32_t)(l + t * LPR);
-        if (idx < nb) grp[idx] = ent[b0 + idx];
-      }
-      strip_sync();
-      // entries [0, ns) of the batch read the staged head buffer, [ns, nb) read X
-      const uint32_t ns = mid > b0 ? (mid - b0 < nb ? mid - b0 : nb) : 0u;
+    if (staged) {
+      const Entry* se = stage + (lo - e0);
+      const uint32_t n = hi - lo, ns = mid > lo ? mid - lo : 0u;
+      // entries [0, ns) read the staged head buffer, [ns, n) read X
       for (int seg = 0; seg < 2; ++seg) {
         const char* base = reinterpret_cast<const char*>(seg == 0 ? Xh : X);
-        const uint32_t j_hi = seg == 0 ? ns : nb;
+        const uint32_t j_hi = seg == 0 ? ns : n;
         for (uint32_t j = seg == 0 ? 0u : ns; j < j_hi; j += UU) {
           Entry e[UU];
           V x[UU];
 #pragma unroll
-          for (int u = 0; u < UU; ++u) e[u] = grp[(j + u) % SG];
+          for (int u = 0; u < UU; ++u) e[u] = se[j + u < j_hi ? j + u : j];
 #pragma unroll
           for (int u = 0; u < UU; ++u)
             x[u] = (j + u < j_hi) ? load_row<VEC, SMALL>(base, e[u].xrow, row_bytes, col_bytes) : vzero<VEC>();
@@ -103,7 +117,34 @@ __global__ __launch_bounds__(kBlock) void rows_kernel(
           for (int u = 0; u < UU; ++u) vfma(acc, (j + u < j_hi) ? e[u].val : 0.f, x[u]);
         }
       }
-      strip_sync();
+    } else {
+      for (uint32_t b0 = lo; b0 < hi; b0 += SG) {
+        const uint32_t nb = hi - b0 < (uint32_t)SG ? hi - b0 : (uint32_t)SG;
+#pragma unroll
+        for (int t = 0; t < SG / LPR; ++t) {
+          const uint32_t idx = (uint32_t)(l + t * LPR);
+          if (idx < nb) grp[idx] = ent[b0 + idx];
+        }
+        strip_sync();
+        // entries [0, ns) of the batch read the staged head buffer, [ns, nb) read X
+        const uint32_t ns = mid > b0 ? (mid - b0 < nb ? mid - b0 : nb) : 0u;
+        for (int seg = 0; seg < 2; ++seg) {
+          const char* base = reinterpret_cast<const char*>(seg == 0 ? Xh : X);
+          const uint32_t j_hi = seg == 0 ? ns : nb;
+          for (uint32_t j = seg == 0 ? 0u : ns; j < j_hi; j += UU) {
+            Entry e[UU];
+            V x[UU];
+#pragma unroll
+            for (int u = 0; u < UU; ++u) e[u] = grp[(j + u) % SG];
+#pragma unroll
+            for (int u = 0; u < UU; ++u)
+              x[u] = (j + u < j_hi) ? load_row<VEC, SMALL>(base, e[u].xrow, row_bytes, col_bytes) : vzero<VEC>();
+#pragma unroll
+            for (int u = 0; u < UU; ++u) vfma(acc, (j + u < j_hi) ? e[u].val : 0.f, x[u]);
+          }
+        }
+        strip_sync();
+      }
     }
     if (col_ok) {
       if (dst >= 0) {
@@ -148,13 +189,20 @@ __global__ __launch_bounds__(kBlock) void chunks_kernel(
   Entry* mine = strip[wave];
   const Entry* grp = mine + g;
   V acc = vzero<VEC>();
+  // the next 64 entries of the chunk are fetched while the current batch is being worked on (the
+  // two segments are consecutive in the entry array, so the fetch runs across their boundary)
+  Entry ahead = ent[lo + lane < hi ? lo + lane : lo];
   for (int seg = 0; seg < 2; ++seg) {
     const char* base = reinterpret_cast<const char*>(seg == 0 ? Xh : X);
     const uint32_t s_lo = seg == 0 ? lo : mid;
     const uint32_t s_hi = seg == 0 ? mid : hi;
     for (uint32_t b0 = s_lo; b0 < s_hi; b0 += 64) {
       const uint32_t nb = s_hi - b0 < 64u ? s_hi - b0 : 64u;
-      if ((uint32_t)lane < nb) mine[lane] = ent[b0 + lane];
+      mine[lane] = ahead;              // entries b0 .. b0 + 63 (those past the chunk's end are not used)
+      {
+        const uint32_t nx = b0 + nb + lane;     // first entry of the next batch, of this or the next segment
+        ahead = ent[nx < hi ? nx : lo];
+      }
       strip_sync();
       uint32_t s = 0;                  // step: lane group g handles entry s * G + g
       for (; (s + U) * G <= nb; s += U) {
