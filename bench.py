@@ -292,6 +292,10 @@ def main() -> int:
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": traffic, "avg_launch_ms": round(avg_ms, 4), "launches_per_step": 1,
                 "algorithmic_bytes_per_launch": int(bytes_per_launch)}
+    if traffic and avg_ms > 0:
+        # the counter bytes over the live launch time, and how much of them the method asks for
+        roofline["counter_GBps"] = round(traffic / (avg_ms * 1e-3) / 1e9, 1)
+        roofline["useful_fraction"] = round(bytes_per_launch / traffic, 4)
 
     # ---- quick correctness sanity + CPU baseline: the oracle on a bounded row sample ----------
     cpu_baseline = None
