@@ -158,6 +158,15 @@ int csf3_build(int64_t I, int64_t J, int64_t K, int64_t nnz, const int32_t* ti, 
       }
     }
     item_seg.push_back((uint32_t)h->n_seg);
+    // the kernel stages an item in fixed-size LDS arrays: make sure no item exceeds them
+    for (size_t t = 0; t + 1 < item_seg.size(); ++t) {
+      const int64_t segs = (int64_t)item_seg[t + 1] - (int64_t)item_seg[t];
+      const int64_t ents = (int64_t)seg_ptr[item_seg[t + 1]] - (int64_t)seg_ptr[item_seg[t]];
+      if (segs < 0 || segs > kItemSegs || ents < 0 || ents > kItemNnz) {
+        delete h;
+        return fail3(ARROW_EINTERNAL, "work item %zu holds %lld segments / %lld entries", t, (long long)segs, (long long)ents);
+      }
+    }
     if (slots > 0x7fffffffLL || item_dst.size() > 0x7fffff00ULL) { delete h; return fail3(ARROW_EINVAL, "too many work items"); }
     h->n_items = (int64_t)item_dst.size();
     h->n_split = (int64_t)split_y.size();

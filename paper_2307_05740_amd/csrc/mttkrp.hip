@@ -53,6 +53,7 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
   if (it >= n_items) return;            // whole wavefront leaves together
   const uint32_t s_lo = item_seg[it], e_lo = item_ent[it];
   const uint32_t n_seg = item_seg[it + 1] - s_lo, n_ent = item_ent[it + 1] - e_lo;
+  if (n_seg > (uint32_t)kCsfItemSegs || n_ent > (uint32_t)kCsfItemNnz) return;   // never true for a built image
   const int lane = threadIdx.x % 64;
   const int g = lane / LPR;
   const int c = (lane % LPR) * VEC + blockIdx.y * (LPR * VEC);

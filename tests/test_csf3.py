@@ -69,3 +69,16 @@ def test_error_paths():
     assert binding.csf3_workspace_bytes(h, 0) == 0
     binding.csf3_destroy(h)
     binding.csf3_destroy(0)
+
+
+def test_items_are_capped_by_segments_as_well_as_entries():
+    # slice 0: 300 fibres of one entry -> 300 segments -> items of at most 128 segments;
+    # slice 1: one fibre of 1000 entries -> 16 segments of <= 64 -> items of at most 512 entries
+    i = np.concatenate([np.zeros(300, np.int32), np.ones(1000, np.int32)])
+    j = np.concatenate([np.arange(300, dtype=np.int32), np.zeros(1000, np.int32)])
+    k = np.concatenate([np.zeros(300, np.int32), np.arange(1000, dtype=np.int32)])
+    info = build_info((3, 300, 1000), i, j, k, np.ones(1300, np.float32))[0]
+    assert info["segments"] == 300 + 16 and info["fibers"] == 301
+    assert info["split_rows"] == 2
+    assert info["partials"] == 3 + 2            # 128 + 128 + 44 segments; 512 + 488 entries
+    assert info["items"] == 3 + 2 + 1           # plus the empty slice 2
