@@ -25,11 +25,15 @@
 //   panel kernels - optional: head-block entries of sparse head rows with the rows'
 //                   accumulators in LDS, one column class per accelerator die
 //   sddmm kernels - the sampled dense-dense product S = A .* (U V^T) over the same lists
-// Both product kernels fetch their entries with one coalesced load per batch,
-// park them in a wavefront-private LDS strip and read them back per lane
-// group, so that U row loads are in flight before the first FMA; the SIMDs
-// are 16 lanes wide (4 cycles per wavefront instruction), so the inner loops
-// are written to need one address instruction per row load.
+// Both product kernels fetch their entries with coalesced loads into LDS (the
+// rows kernel all entries of a workgroup's items at once, the chunk kernel 64
+// at a time into a wavefront-private strip, the next 64 already on their way)
+// and read them back per lane group, so that U row loads are in flight before
+// the first FMA and a lane group only ever waits for the rows it gathers; the
+// SIMDs are 16 lanes wide (4 cycles per wavefront instruction), so the inner
+// loops are written to need one address instruction per row load.
+// Rows written or read exactly once per product (results, partial vectors)
+// carry the non-temporal hint and leave the L2 to the rows of X.
 // No floating-point atomics: results are bitwise reproducible run to run.
 #include <hip/hip_runtime.h>
 
