@@ -215,7 +215,8 @@ int arrow_self_check(const arrow_handle *h);
  * this many entries is handled by a lane group instead of a wavefront, default 48), ARROW_STAGE_HEAD (1: the head rows of level 0 are gathered into a
  * contiguous buffer before the product), ARROW_STAGE_SHORT (1 / 0: the short rows read their head
  * columns from that buffer as well / from X; default -1 = from the buffer when the head vertices are
- * scattered over X), ARROW_WINDOW_SPAN (widest column span of a diagonal-block tile whose
+ * scattered over X), ARROW_EMPTY_LAST (1, the default: the rows of level 0 without entries, which only
+ * store zeros, are listed after all other short rows), ARROW_WINDOW_SPAN (widest column span of a diagonal-block tile whose
  * window of P_i X is staged in LDS, default 2048, at most 4096, 0 = no such tiles),
  * ARROW_WINDOW_TILE_ROWS (most rows per tile, default 1024), ARROW_WINDOW_REUSE_X10 (a tile is
  * kept when its diagonal-block entries number at least this / 10 times its span, default 80),

@@ -257,6 +257,7 @@ void read_pack_options(arrow_handle* h) {
   h->pack.piece_max = (int32_t)env_int("ARROW_PIECE_MAX", h->pack.piece_max);
   h->pack.stage_head = (int32_t)env_int("ARROW_STAGE_HEAD", h->pack.stage_head);
   h->pack.stage_short = (int32_t)env_int("ARROW_STAGE_SHORT", h->pack.stage_short);
+  h->pack.empty_last = (int32_t)env_int("ARROW_EMPTY_LAST", h->pack.empty_last);
   h->pack.panel = (int32_t)env_int("ARROW_PANEL", h->pack.panel);
   h->pack.panel_min = (int32_t)env_int("ARROW_PANEL_MIN", h->pack.panel_min);
   h->pack.window_span = (int32_t)env_int("ARROW_WINDOW_SPAN", h->pack.window_span);

@@ -121,6 +121,7 @@ struct PackOptions {
   int32_t piece_max = 48;     // a class piece with at most this many entries is a group-list item
   int32_t stage_head = 1;     // gather the head rows of level 0 into a contiguous buffer
   int32_t stage_short = -1;   // short rows read their head columns from the staged head too (-1 = when the head is scattered over X)
+  int32_t empty_last = 1;     // level 0: the short rows without entries are listed after all others
   int32_t panel = 0;          // run the head block of sparse head rows in panels (accumulators in LDS, one column class per die)
   int32_t panel_min = 8;      // fewest head-block entries of a row that joins a panel
   int32_t window_span = 2048; // widest column span of an LDS-window tile (0 = no such tiles)

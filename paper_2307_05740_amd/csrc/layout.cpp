@@ -335,6 +335,14 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
       P.row_pos.push_back((int32_t)p);
     }
 
+    // the rows without entries (level 0 lists them: it stores every row of Y) go last, so that
+    // their zero stores do not run between the gathers of the other rows
+    if (opt.empty_last && li == 0) {
+      std::stable_partition(P.row_pos.begin(), P.row_pos.end(), [&](int32_t p) {
+        return L.rowptr[p + 1] - L.rowptr[p] - (int64_t)P.row_skip(p) > 0;
+      });
+    }
+
     // ---- items of the long rows, row by row ---------------------------------------------------
     const int64_t n_long = (int64_t)P.long_rows.size();
     P.row_split.assign(n_long, 0);
