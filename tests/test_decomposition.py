@@ -215,6 +215,8 @@ def test_error_paths():
     dict(ARROW_PANEL="1", ARROW_WINDOW_ROWS="32", ARROW_PANEL_MIN="1", ARROW_SHORT_MAX="0"),
     dict(ARROW_PANEL="1", ARROW_WINDOW_ROWS="128", ARROW_CHUNK_MIN="16", ARROW_HEAD_BY_ID="0"),
     dict(ARROW_WINDOW_ROWS="64", ARROW_HEAD_BY_ID="0"),
+    dict(ARROW_STAGE_SHORT="1"), dict(ARROW_STAGE_SHORT="0", ARROW_EMPTY_LAST="0"),
+    dict(ARROW_STAGE_SHORT="1", ARROW_EMPTY_LAST="1", ARROW_SHORT_MAX="64", ARROW_CLASSES="8", ARROW_CLASS_MIN="2"),
 ])
 def test_packed_image_self_check_under_pack_options(monkeypatch, env):
     for name, v in env.items():

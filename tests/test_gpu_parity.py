@@ -124,6 +124,9 @@ def test_pack_options_short_and_chunk(torch, monkeypatch):
     dict(ARROW_CLASSES="16", ARROW_CLASS_MIN="2", ARROW_PIECE_MAX="0"),
     dict(ARROW_CLASSES="16", ARROW_CLASS_MIN="2", ARROW_PIECE_MAX="1000000", ARROW_CLASS_GRAN="32"),
     dict(ARROW_CLASSES="8", ARROW_CLASS_MIN="3", ARROW_PIECE_MAX="5", ARROW_SHORT_MAX="2"),
+    dict(ARROW_STAGE_SHORT="1", ARROW_EMPTY_LAST="1"),
+    dict(ARROW_STAGE_SHORT="0", ARROW_EMPTY_LAST="0"),
+    dict(ARROW_STAGE_SHORT="1", ARROW_SHORT_MAX="64", ARROW_CLASSES="8", ARROW_CLASS_MIN="2"),
 ])
 @pytest.mark.parametrize("k", [16, 128, 36])
 def test_die_queues_and_head_staging(torch, monkeypatch, env, k):
