@@ -6,22 +6,30 @@
 // following peeling, repeated on the entries no earlier level has taken:
 //   1. degree of a vertex = its remaining off-diagonal entries, row plus column;
 //      the active vertices are those with any remaining entry (level 0: all).
+//      Two vertices are adjacent when the remainder holds an entry between
+//      them in either direction (the pattern of R + R^T): a directed operand
+//      gets the transposed pattern built once per level, a symmetric pattern
+//      (tested once, on the operand) is its own transpose at every level.
 //   2. the remaining vertices are put in a linear arrangement: ascending id at
-//      level 0, breadth-first order over the remainder at later levels.
+//      level 0, breadth-first order over the adjacency at later levels.
 //   3. head (positions 0..b-1), one of two rules:
 //        separator rule - hubs (degree > hub_factor * mean) first, then walk
-//          the arrangement filling blocks of b; a vertex with an entry into an
-//          already closed block is moved to the head.  If the head does not
-//          overflow, the level captures every remaining entry; spare head
+//          the arrangement filling blocks of b; a vertex adjacent to a vertex
+//          of an already closed block is moved to the head.  If the head does
+//          not overflow, every remaining entry has an end in the head or both
+//          ends in one block (the later end of an entry was either promoted or
+//          placed while the earlier end's block was still open); spare head
 //          positions are filled from the end of the arrangement, which moves
-//          no block boundary.
+//          no block boundary.  The rule is accepted only after a count shows
+//          that the level really takes every remaining entry.
 //        plain rule - the b vertices of highest degree (ties: lower id first);
 //          everything else keeps its arrangement order and is cut into blocks.
 //   4. an entry (u,v) belongs to the level iff pos(u) < b or pos(v) < b or
 //      pos(u)/b == pos(v)/b; the others form the next remainder.
-// The plain rule always captures every entry of the maximum-degree vertex, so
-// each level removes at least one entry and the loop ends.  Values are moved,
-// never combined: every stored entry of A appears in exactly one level.
+// The plain rule always captures every entry of the maximum-degree vertex, in
+// either direction, so each level removes at least one entry and the loop ends.
+// Values are moved, never combined: every stored entry of A appears in exactly
+// one level.
 #include "arrow_internal.h"
 
 #include <omp.h>
@@ -48,8 +56,85 @@ struct Remainder {
   int64_t nnz(int64_t n) const { return ptr[n]; }
 };
 
-// breadth-first arrangement of the active vertices over the remainder's rows
-void bfs_order(int64_t n, const Remainder& R, const std::vector<uint8_t>& active,
+// true when every off-diagonal entry (u,v) of the pattern has its mirror (v,u)
+bool pattern_symmetric(int64_t n, const Remainder& R) {
+  int asym = 0;
+#pragma omp parallel for schedule(dynamic, 4096)
+  for (int64_t u = 0; u < n; ++u) {
+    if (__atomic_load_n(&asym, __ATOMIC_RELAXED)) continue;
+    for (int64_t p = R.ptr[u]; p < R.ptr[u + 1]; ++p) {
+      const int32_t w = R.col[p];
+      if (w == u) continue;
+      if (!std::binary_search(R.col + R.ptr[w], R.col + R.ptr[w + 1], (int32_t)u)) {
+        __atomic_store_n(&asym, 1, __ATOMIC_RELAXED);
+        break;
+      }
+    }
+  }
+  return asym == 0;
+}
+
+// Neighbours of a vertex in the pattern of R + R^T.  For a symmetric pattern the rows of R are
+// the whole adjacency.  Otherwise the transposed pattern (row v = the rows u that hold an entry
+// (u,v)) is built from the column counts and merged, row by row, with R's: a vertex's neighbours
+// are then the ascending union of both, so an operand and its transpose are arranged alike.
+struct Adjacency {
+  const int64_t* ptr = nullptr;
+  const int32_t* col = nullptr;
+  std::vector<int64_t> own_ptr;
+  std::vector<int32_t> own_col;
+
+  void build(int64_t n, const Remainder& rem, bool symmetric, const std::vector<int32_t>& colcnt) {
+    if (symmetric) { ptr = rem.ptr; col = rem.col; return; }
+    std::vector<int64_t> tptr(n + 1, 0);
+    for (int64_t v = 0; v < n; ++v) tptr[v + 1] = tptr[v] + colcnt[v];
+    std::vector<int32_t> tcol(tptr[n]);
+    {
+      std::vector<int64_t> fill(tptr.begin(), tptr.end() - 1);
+#pragma omp parallel for schedule(dynamic, 4096)
+      for (int64_t u = 0; u < n; ++u)
+        for (int64_t p = rem.ptr[u]; p < rem.ptr[u + 1]; ++p) {
+          const int64_t at = __atomic_fetch_add(&fill[rem.col[p]], 1, __ATOMIC_RELAXED);
+          tcol[at] = (int32_t)u;
+        }
+    }
+    // the atomic fill leaves a row in arrival order; sorting makes the result deterministic
+#pragma omp parallel for schedule(dynamic, 4096)
+    for (int64_t v = 0; v < n; ++v) std::sort(tcol.begin() + tptr[v], tcol.begin() + tptr[v + 1]);
+    // union of the two sorted rows: count, prefix sum, fill
+    own_ptr.assign(n + 1, 0);
+    auto merge_row = [&](int64_t u, int32_t* out) -> int64_t {
+      const int32_t* a = rem.col + rem.ptr[u];
+      const int32_t* ae = rem.col + rem.ptr[u + 1];
+      const int32_t* t = tcol.data() + tptr[u];
+      const int32_t* te = tcol.data() + tptr[u + 1];
+      int64_t cnt = 0;
+      while (a < ae || t < te) {
+        int32_t w;
+        if (t == te || (a < ae && *a < *t)) w = *a++;
+        else if (a == ae || *t < *a) w = *t++;
+        else { w = *a; ++a; ++t; }
+        if (out) out[cnt] = w;
+        ++cnt;
+      }
+      return cnt;
+    };
+#pragma omp parallel for schedule(dynamic, 4096)
+    for (int64_t u = 0; u < n; ++u) own_ptr[u + 1] = merge_row(u, nullptr);
+    for (int64_t u = 0; u < n; ++u) own_ptr[u + 1] += own_ptr[u];
+    own_col.resize(own_ptr[n]);
+#pragma omp parallel for schedule(dynamic, 4096)
+    for (int64_t u = 0; u < n; ++u) merge_row(u, own_col.data() + own_ptr[u]);
+    ptr = own_ptr.data();
+    col = own_col.data();
+  }
+  int64_t degree_slots(int32_t u) const { return ptr[u + 1] - ptr[u]; }
+  // the s-th neighbour of u, s < degree_slots(u) (u itself is listed when it has a diagonal entry)
+  int32_t at(int32_t u, int64_t s) const { return col[ptr[u] + s]; }
+};
+
+// breadth-first arrangement of the active vertices over the adjacency
+void bfs_order(int64_t n, const Adjacency& adj, const std::vector<uint8_t>& active,
                std::vector<int32_t>& order) {
   std::vector<uint8_t> seen(n, 0);
   order.clear();
@@ -60,40 +145,42 @@ void bfs_order(int64_t n, const Remainder& R, const std::vector<uint8_t>& active
     seen[s] = 1;
     while (head < order.size()) {
       int32_t u = order[head++];
-      for (int64_t p = R.ptr[u]; p < R.ptr[u + 1]; ++p) {
-        int32_t w = R.col[p];
+      const int64_t ds = adj.degree_slots(u);
+      for (int64_t s2 = 0; s2 < ds; ++s2) {
+        int32_t w = adj.at(u, s2);
         if (!seen[w] && active[w]) { seen[w] = 1; order.push_back(w); }
       }
     }
   }
 }
 
-// Arrangement of the vertices outside `skip` (the head) by a traversal that ignores every
+// Arrangement of the vertices outside `skip` (the head) by a traversal of the adjacency that ignores every
 // entry touching a skipped vertex: depth-first preorder (dfs) or breadth-first order.  Sparse
 // remainders are mostly small trees; a preorder keeps each of them contiguous, so most of their
 // entries end up inside one diagonal block.
-void traversal_order(int64_t n, const Remainder& R, const std::vector<uint8_t>& active,
+void traversal_order(int64_t n, const Adjacency& adj, const std::vector<uint8_t>& active,
                      const std::vector<uint8_t>& skip, bool dfs, std::vector<int32_t>& order) {
   std::vector<uint8_t> seen(n, 0);
   order.clear();
-  std::vector<std::pair<int32_t, int64_t>> stack;   // vertex, next entry to look at
+  std::vector<std::pair<int32_t, int64_t>> stack;   // vertex, next neighbour slot to look at
   for (int64_t s = 0; s < n; ++s) {
     if (!active[s] || skip[s] || seen[s]) continue;
     seen[s] = 1;
     order.push_back((int32_t)s);
     if (dfs) {
       stack.clear();
-      stack.emplace_back((int32_t)s, R.ptr[s]);
+      stack.emplace_back((int32_t)s, (int64_t)0);
       while (!stack.empty()) {
         auto& top = stack.back();
         const int32_t u = top.first;
         bool pushed = false;
-        while (top.second < R.ptr[u + 1]) {
-          const int32_t w = R.col[top.second++];
+        const int64_t ds = adj.degree_slots(u);
+        while (top.second < ds) {
+          const int32_t w = adj.at(u, top.second++);
           if (!seen[w] && active[w] && !skip[w]) {
             seen[w] = 1;
             order.push_back(w);
-            stack.emplace_back(w, R.ptr[w]);
+            stack.emplace_back(w, (int64_t)0);
             pushed = true;
             break;
           }
@@ -104,8 +191,9 @@ void traversal_order(int64_t n, const Remainder& R, const std::vector<uint8_t>& 
       size_t head = order.size() - 1;
       while (head < order.size()) {
         const int32_t u = order[head++];
-        for (int64_t p = R.ptr[u]; p < R.ptr[u + 1]; ++p) {
-          const int32_t w = R.col[p];
+        const int64_t ds = adj.degree_slots(u);
+        for (int64_t s2 = 0; s2 < ds; ++s2) {
+          const int32_t w = adj.at(u, s2);
           if (!seen[w] && active[w] && !skip[w]) { seen[w] = 1; order.push_back(w); }
         }
       }
@@ -128,6 +216,8 @@ int decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const flo
   std::vector<uint8_t> active(n);
   std::vector<int32_t> order;
   const int64_t level_cap = 4 * ((n + b - 1) / b) + 64;
+  const bool symmetric = pattern_symmetric(n, R);   // the remainders of a symmetric pattern stay symmetric
+  Adjacency adj;
 
   for (int64_t lev = 0;; ++lev) {
     const int64_t rem_nnz = R.nnz(n);
@@ -152,6 +242,8 @@ int decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const flo
       if (a) { ++n_i; deg_sum += (double)deg[u]; }
     }
 
+    adj.build(n, R, symmetric, colcnt);
+
     HostLevel L;
     L.n_i = n_i;
     L.perm.resize(n_i);
@@ -166,7 +258,7 @@ int decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const flo
       order.reserve(n_i);
       for (int64_t u = 0; u < n; ++u) if (active[u]) order.push_back((int32_t)u);
     } else {
-      bfs_order(n, R, active, order);
+      bfs_order(n, adj, active, order);
     }
 
     // ---- 3. head and block positions ------------------------------------
@@ -193,8 +285,9 @@ int decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const flo
           for (int32_t v : order) {
             if (blk[v] == 0) continue;
             bool promote = false;
-            for (int64_t p = R.ptr[v]; p < R.ptr[v + 1]; ++p) {
-              int32_t bw = blk[R.col[p]];
+            const int64_t ds = adj.degree_slots(v);
+            for (int64_t s2 = 0; s2 < ds; ++s2) {
+              int32_t bw = blk[adj.at(v, s2)];
               if (bw >= 1 && bw < cur) { promote = true; break; }
             }
             if (promote) {
@@ -214,8 +307,25 @@ int decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const flo
             for (int32_t v : seps) L.perm[h++] = v;
             for (int64_t t = 0; t < need; ++t) { L.perm[h++] = body.back(); body.pop_back(); }
             for (int32_t v : body) L.perm[h++] = v;
-            L.separator_rule = true;
-            done = true;
+            // accept only if the level takes every remaining entry (it must, by the argument in
+            // the header; the count guards the rule against any operand the argument misses)
+            std::vector<int32_t> spos(n, -1);
+#pragma omp parallel for schedule(static)
+            for (int64_t p = 0; p < n_i; ++p) spos[L.perm[p]] = (int32_t)p;
+            int64_t outside = 0;
+#pragma omp parallel for schedule(dynamic, 4096) reduction(+ : outside)
+            for (int64_t u = 0; u < n; ++u) {
+              const int64_t pu = spos[u];
+              if (pu < 0 || pu < b) continue;
+              for (int64_t p = R.ptr[u]; p < R.ptr[u + 1]; ++p) {
+                const int64_t pv = spos[R.col[p]];
+                if (pv >= b && pv / b != pu / b) ++outside;
+              }
+            }
+            if (outside == 0) {
+              L.separator_rule = true;
+              done = true;
+            }
           }
         }
       }
@@ -238,7 +348,7 @@ int decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const flo
             trial.clear();
             for (int32_t v : order) if (!in_head[v]) trial.push_back(v);
           } else {
-            traversal_order(n, R, active, in_head, cnd == 1, trial);
+            traversal_order(n, adj, active, in_head, cnd == 1, trial);
           }
           const int64_t nt = (int64_t)trial.size();
 #pragma omp parallel for schedule(static)

@@ -156,6 +156,147 @@ def test_nonsymmetric_operand():
     full_check(rp, ci, va, 7, rng.standard_normal((n, 3)).astype(np.float32))
 
 
+def _directed(n, rows, cols, seed=11):
+    rng = np.random.default_rng(seed)
+    rp, ci, va = csr_from_coo(n, np.asarray(rows), np.asarray(cols), rng.uniform(-1, 1, len(rows)))
+    return rp, ci, va, rng.standard_normal((n, 3)).astype(np.float32)
+
+
+@pytest.mark.parametrize("n,b,off,cnt", [(4096, 64, 2048, 2048 - 64), (64, 4, 32, 28),
+                                         (4096, 64, 100, 4096 - 300)])
+@pytest.mark.parametrize("lower", [False, True])
+def test_directed_shift_operands(n, b, off, cnt, lower):
+    """Entries (i, i + off) only -- strictly upper (or, mirrored, strictly lower) triangular, every
+    vertex with one entry in its row or one in its column but seldom both.  Adjacency has to be
+    taken from the pattern of A + A^T: a rule that follows rows alone finds nothing to do for the
+    column ends.  Both orientations must decompose, into the same small number of levels."""
+    i = np.arange(cnt)
+    r, c = (i + off, i) if lower else (i, i + off)
+    rp, ci, va, X = _directed(n, r, c)
+    info, linfo, _ = full_check(rp, ci, va, b, X)
+    assert info["levels"] <= 2
+    assert linfo[0]["nnz"] >= 0.9 * cnt
+
+
+def test_directed_strictly_triangular_random_and_long_cycle():
+    rng = np.random.default_rng(8)
+    n = 600
+    M = np.triu(rng.random((n, n)) < 0.01, k=1)
+    r, c = np.nonzero(M)
+    for b in (8, 50):
+        rp, ci, va, X = _directed(n, r, c)
+        info, _, _ = full_check(rp, ci, va, b, X)
+        rp, ci, va, X = _directed(n, c, r)                   # the transposed operand
+        info_t, _, _ = full_check(rp, ci, va, b, X)
+        assert info["levels"] == info_t["levels"]           # the rules only see A + A^T
+    # one directed cycle through all vertices in a scrambled order, much longer than b
+    n, b = 1000, 16
+    order = rng.permutation(n)
+    rp, ci, va, X = _directed(n, order, np.roll(order, -1))
+    info, linfo, _ = full_check(rp, ci, va, b, X)
+    assert info["levels"] <= 3 and linfo[0]["nnz"] >= 0.9 * n
+
+
+def test_random_directed_operands_always_decompose():
+    rng = np.random.default_rng(2024)
+    for trial in range(60):
+        n = int(rng.integers(2, 300))
+        b = int(rng.integers(1, 40))
+        m = int(rng.integers(0, 4 * n))
+        r = rng.integers(0, n, m)
+        c = rng.integers(0, n, m)
+        if trial % 3 == 0:
+            r, c = np.minimum(r, c), np.maximum(r, c)         # upper triangular with diagonal
+        key = np.unique(r * n + c)
+        rp, ci, va, X = _directed(n, key // n, key % n, seed=trial)
+        info, _, _ = full_check(rp, ci, va, b, X)
+        assert info["levels"] <= 4 * ((n + b - 1) // b) + 64
+
+
+# --- the invariant checkers themselves: each must reject a violating level -------------------
+
+def _valid_small_level():
+    """n = 6, b = 2, one level holding the whole of a small matrix: positions are a rotation of
+    the vertex ids; entries sit in the head row, the head column and the diagonal blocks."""
+    n, b = 6, 2
+    perm = np.array([4, 5, 0, 1, 2, 3], np.int32)
+    r = np.array([0, 0, 1, 2, 3, 3, 4, 5, 5], np.int32)     # positions
+    c = np.array([0, 5, 3, 3, 2, 0, 5, 4, 1], np.int32)
+    v = np.arange(1, 10, dtype=np.float32) / 8
+    rows, cols = perm[r], perm[c]
+    rp, ci, va = csr_from_coo(n, rows.astype(np.int64), cols.astype(np.int64), v.astype(np.float64))
+    return n, b, rp, ci, va, (perm, r, c, v)
+
+
+def test_checkers_accept_a_valid_hand_made_level():
+    n, b, rp, ci, va, lev = _valid_small_level()
+    arrow_checks.check_decomposition(n, rp, ci, va, b, [lev])
+
+
+def test_check_arrow_shape_rejects_an_entry_outside_the_arrow():
+    n, b, rp, ci, va, (perm, r, c, v) = _valid_small_level()
+    r2, c2 = r.copy(), c.copy()
+    r2[3], c2[3] = 2, 4                                      # blocks 1 and 2, neither in the head
+    with pytest.raises(AssertionError, match="outside the arrow"):
+        arrow_checks.check_arrow_shape(r2, c2, b, len(perm))
+    arrow_checks.check_arrow_shape(r2, c2, 3, len(perm))     # 2 // 3 = 0: first block row at b = 3
+    c3 = c.copy()
+    c3[0] = len(perm)                                        # a position outside the level
+    with pytest.raises(AssertionError, match="outside the level"):
+        arrow_checks.check_arrow_shape(r, c3, b, len(perm))
+    with pytest.raises(AssertionError):                      # ... and through the front door
+        arrow_checks.check_decomposition(n, rp, ci, va, b, [(perm, r2, c2, v)])
+
+
+def test_check_perm_injective_rejects_duplicates_and_out_of_range():
+    n, b, rp, ci, va, (perm, r, c, v) = _valid_small_level()
+    dup = perm.copy()
+    dup[5] = dup[0]
+    with pytest.raises(AssertionError, match="injective"):
+        arrow_checks.check_perm_injective(dup, n)
+    far = perm.copy()
+    far[2] = n
+    with pytest.raises(AssertionError, match="out of range"):
+        arrow_checks.check_perm_injective(far, n)
+    neg = perm.copy()
+    neg[2] = -1
+    with pytest.raises(AssertionError, match="out of range"):
+        arrow_checks.check_perm_injective(neg, n)
+    with pytest.raises(AssertionError):
+        arrow_checks.check_decomposition(n, rp, ci, va, b, [(dup, r, c, v)])
+
+
+def test_check_reassembly_rejects_flipped_bits_dropped_moved_and_split_entries():
+    n, b, rp, ci, va, (perm, r, c, v) = _valid_small_level()
+    flipped = v.copy()
+    flipped.view(np.uint32)[4] ^= 1                           # one mantissa bit
+    with pytest.raises(AssertionError, match="value bits"):
+        arrow_checks.check_reassembly(n, rp, ci, va, [(perm, r, c, flipped)])
+    negz = v.copy()
+    with pytest.raises(AssertionError, match="entry count"):  # a dropped entry
+        arrow_checks.check_reassembly(n, rp, ci, va, [(perm, r[:-1], c[:-1], v[:-1])])
+    moved = c.copy()
+    moved[6] = 4                                              # same count, other coordinate
+    with pytest.raises(AssertionError, match="coordinates"):
+        arrow_checks.check_reassembly(n, rp, ci, va, [(perm, r, moved, v)])
+    # an entry split into two halves in two levels sums to A but is not a reassembly
+    half = v.copy()
+    half[2] /= 2
+    second = (perm, r[2:3], c[2:3], half[2:3])
+    with pytest.raises(AssertionError):
+        arrow_checks.check_reassembly(n, rp, ci, va, [(perm, r, c, half), second])
+    # the same entry in two levels
+    with pytest.raises(AssertionError, match="entry count"):
+        arrow_checks.check_reassembly(n, rp, ci, va, [(perm, r, c, v), (perm, r[:1], c[:1], v[:1])])
+    # signed zero is a different bit pattern
+    rp0, ci0, va0 = csr_from_coo(2, np.array([0]), np.array([1]), np.array([0.0]))
+    lev = (np.array([0, 1], np.int32), np.array([0], np.int32), np.array([1], np.int32),
+           np.array([-0.0], np.float32))
+    with pytest.raises(AssertionError, match="value bits"):
+        arrow_checks.check_reassembly(2, rp0, ci0, va0, [lev])
+    del negz
+
+
 def test_empty_matrix_and_explicit_zeros():
     n = 10
     rp = np.zeros(n + 1, np.int64)

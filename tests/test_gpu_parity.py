@@ -288,6 +288,50 @@ def test_hub_row_is_split_and_reduced(torch):
     op.close()
 
 
+def _csr(n, rows, cols, seed):
+    key = np.unique(np.asarray(rows, np.int64) * n + np.asarray(cols, np.int64))
+    rows, cols = key // n, key % n
+    rowptr = np.zeros(n + 1, np.int64)
+    np.add.at(rowptr, rows + 1, 1)
+    rowptr = np.cumsum(rowptr)
+    colidx = cols.astype(np.int32)
+    return rowptr, colidx, synth.fill_uniform(rowptr, colidx, seed=seed)
+
+
+@pytest.mark.parametrize("lower", [False, True])
+def test_directed_operands(torch, lower):
+    """Non-symmetric operands: a pure shift (strictly triangular, every vertex has a row entry or
+    a column entry, seldom both), and a strictly triangular random pattern with a few full rows.
+    The decomposition takes adjacency from A + A^T; the product must still be A X, not A^T X."""
+    n, b, k = 4096, 64, 20
+    i = np.arange(n - 300)
+    r, c = (i + 100, i) if lower else (i, i + 100)
+    csr = _csr(n, r, c, seed=31)
+    X = synth.normal_matrix(n, k, seed=32)
+    op, _, Y = run_product(torch, csr, b, X)
+    assert op.info["levels"] <= 2
+    Yref, B = oracle.spmm(*csr, X)
+    assert_within(Y, Yref, B)
+    op.close()
+    rng = np.random.default_rng(33)
+    n, b, k = 20000, 256, 36
+    m = 16 * n
+    r = rng.integers(0, n, m)
+    c = rng.integers(0, n, m)
+    hubs = rng.integers(0, n, 5)
+    r = np.concatenate([r, np.repeat(hubs, n // 2)])
+    c = np.concatenate([c, rng.integers(0, n, 5 * (n // 2))])
+    keep = (r > c) if lower else (r < c)
+    csr = _csr(n, r[keep], c[keep], seed=34)
+    X = synth.normal_matrix(n, k, seed=35)
+    op, _, Y = run_product(torch, csr, b, X)
+    levels = [binding.arrow_export_level(op.h, i) for i in range(op.info["levels"])]
+    arrow_checks.check_decomposition(n, *csr, b, levels)
+    Yref, B = oracle.spmm(*csr, X)
+    assert_within(Y, Yref, B)
+    op.close()
+
+
 def test_special_operands_bitwise(torch):
     rng = np.random.default_rng(3)
     n, k = 3000, 12
