@@ -151,8 +151,9 @@ int arrow_set_workspace(arrow_handle *h, void *dev_ws, size_t bytes);
  * With profiling off the call only launches kernels on `stream` (no allocation, no memset, no
  * synchronisation), so it may be recorded into a HIP graph by a caller that captures `stream`;
  * the same holds for arrow_spmm_iter (plus one device-to-device copy for odd l) and arrow_sddmm.
- * Errors: EINVAL (NULL, k < 1, X == Y), ENOTREADY, ETOOSMALL (workspace bound
- * for a smaller k), EHIP.
+ * Errors: EINVAL (NULL, k < 1, misaligned; the byte ranges of X and Y overlap each other or the
+ * bound workspace, or Y overlaps the device image), ENOTREADY, ETOOSMALL (workspace bound for a
+ * smaller k), EHIP.
  */
 int arrow_spmm(arrow_handle *h, const float *X, float *Y, int32_t k, void *stream);
 

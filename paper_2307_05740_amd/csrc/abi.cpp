@@ -113,6 +113,26 @@ struct Scoped {
   }
 };
 
+bool ranges_overlap(const void* a, size_t a_bytes, const void* b, size_t b_bytes) {
+  const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+  return a_bytes && b_bytes && a0 < b0 + b_bytes && b0 < a0 + a_bytes;
+}
+
+// X (read) and Y (written) of a product must be disjoint from each other, from the scratch memory
+// the product writes and from the packed image it reads
+int check_operands(const arrow_handle* h, const float* X, float* Y, int32_t k, const unsigned char* ws,
+                   size_t ws_bytes) {
+  if (!X || !Y) return fail(ARROW_EINVAL, "X or Y is NULL");
+  if (((uintptr_t)X | (uintptr_t)Y) % 16) return fail(ARROW_EINVAL, "X and Y must be 16-byte aligned");
+  const size_t xy = (size_t)h->n * (size_t)k * sizeof(float);
+  if (ranges_overlap(X, xy, Y, xy)) return fail(ARROW_EINVAL, "X and Y must not overlap");
+  if (ranges_overlap(X, xy, ws, ws_bytes) || ranges_overlap(Y, xy, ws, ws_bytes))
+    return fail(ARROW_EINVAL, "X and Y must not overlap the workspace");
+  if (ranges_overlap(Y, xy, h->dev, h->img.bytes.size()))
+    return fail(ARROW_EINVAL, "Y must not overlap the device image");
+  return ARROW_OK;
+}
+
 int check_hip(int rc, const char* what) {
   if (rc == 0) return ARROW_OK;
   return fail(ARROW_EHIP, "%s: %s", what, hipGetErrorString((hipError_t)rc));
@@ -428,9 +448,8 @@ int arrow_set_workspace(arrow_handle* h, void* dev_ws, size_t bytes) {
 int arrow_spmm(arrow_handle* h, const float* X, float* Y, int32_t k, void* stream) {
   int rc = ready(h, k, false);
   if (rc) return rc;
-  if (!X || !Y) return fail(ARROW_EINVAL, "X or Y is NULL");
-  if (X == Y) return fail(ARROW_EINVAL, "X and Y must not overlap");
-  if (((uintptr_t)X | (uintptr_t)Y) % 16) return fail(ARROW_EINVAL, "X and Y must be 16-byte aligned");
+  rc = check_operands(h, X, Y, k, h->ws, h->ws_bytes);
+  if (rc) return rc;
   h->spans_used = 0;
   return product(h, X, Y, k, (hipStream_t)stream);
 }
@@ -441,6 +460,9 @@ int arrow_spmm_iter(arrow_handle* h, float* X, int32_t k, int32_t l, void* strea
   if (rc) return rc;
   if (!X) return fail(ARROW_EINVAL, "X is NULL");
   if ((uintptr_t)X % 16) return fail(ARROW_EINVAL, "X must be 16-byte aligned");
+  if (ranges_overlap(X, (size_t)h->n * (size_t)k * sizeof(float), h->ws, h->ws_bytes) ||
+      ranges_overlap(X, (size_t)h->n * (size_t)k * sizeof(float), h->dev, h->img.bytes.size()))
+    return fail(ARROW_EINVAL, "X must not overlap the workspace or the device image");
   if (l == 0) return ARROW_OK;
   h->spans_used = 0;
   float* tmp = reinterpret_cast<float*>(h->ws + partial_bytes(h, k) + stage_bytes(h, k) + panel_bytes(h, k));

@@ -417,6 +417,15 @@ def test_errors_on_device(torch):
     with pytest.raises(binding.ArrowError) as ei:                     # in place is refused
         binding.arrow_spmm(op.h, Xd.data_ptr(), Xd.data_ptr(), 8, 0)
     assert ei.value.code == binding.ARROW_EINVAL
+    # partial overlap of X and Y, and operands inside the workspace, are refused as well
+    big = torch.zeros((2 * w.n, 8), device="cuda")
+    half = big.data_ptr() + w.n * 8 * 4 // 2
+    half -= half % 16
+    for x_ptr, y_ptr in ((big.data_ptr(), half), (half, big.data_ptr()),
+                         (Xd.data_ptr(), op._ws.data_ptr()), (op._ws.data_ptr() + 256, big.data_ptr())):
+        with pytest.raises(binding.ArrowError) as ei:
+            binding.arrow_spmm(op.h, x_ptr, y_ptr, 8, 0)
+        assert ei.value.code == binding.ARROW_EINVAL and "overlap" in str(ei.value)
     with pytest.raises(binding.ArrowError) as ei:                     # workspace bound for k = 8 only
         binding.arrow_spmm_iter(op.h, Xd.data_ptr(), 64, 2, 0)
     assert ei.value.code == binding.ARROW_ETOOSMALL
