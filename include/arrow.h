@@ -158,6 +158,27 @@ int arrow_set_workspace(arrow_handle *h, void *dev_ws, size_t bytes);
 int arrow_spmm(arrow_handle *h, const float *X, float *Y, int32_t k, void *stream);
 
 /*
+ * arrow_spmm for callers that cannot allocate or own device scratch memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same product, same kernels and
+ * same results bit for bit as arrow_spmm, but the partial vectors and the staged head rows live
+ * in a device array of ARROW_STATIC_SCRATCH_BYTES that is part of the library itself (one copy
+ * per GPU, held until the process ends), so no workspace has to be bound (arrow_upload must have
+ * run on the current device).  The call allocates nothing, records no events even when profiling
+ * is on, and only launches kernels on `stream`.
+ *   X, Y    DEVICE, n x k fp32 row-major, 16-byte aligned, must not overlap; Y is overwritten
+ * The scratch need is arrow_workspace_bytes(h, k) minus the n x k buffer of the chained products
+ * (partial vectors of the largest level + min(b, n) staged head rows of k floats); if it exceeds
+ * the array the call fails with ARROW_ETOOSMALL and nothing is launched.  All calls on one GPU
+ * share that GPU's array, whatever the handle or stream: calls that overlap in time on one GPU
+ * race and give wrong results; calls in stream order are safe.  Nothing in the array has to start
+ * at zero (every slot a product reads was written earlier in the same product), so the previous
+ * call's contents do not matter.
+ * Errors: EINVAL (NULL, k < 1, overlapping X and Y, alignment), ENOTREADY (no image), ETOOSMALL, EHIP.
+ */
+#define ARROW_STATIC_SCRATCH_BYTES (64u << 20)
+int arrow_spmm_static(arrow_handle *h, const float *X, float *Y, int32_t k, void *stream);
+
+/*
  * X <- A^l . X, l chained products rounded to fp32 after each one, result left
  * in X (l = 0 leaves X untouched).  Uses the n x k part of the workspace.
  * Errors as arrow_spmm, plus EINVAL for l < 0.

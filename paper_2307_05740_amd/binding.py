@@ -22,7 +22,7 @@ ARROW_OK, ARROW_EINVAL, ARROW_ENOMEM, ARROW_ENOTREADY, ARROW_ETOOSMALL, ARROW_EH
 
 EXPORTED = [
     "arrow_decompose", "arrow_device_bytes", "arrow_upload", "arrow_workspace_bytes",
-    "arrow_set_workspace", "arrow_spmm", "arrow_spmm_iter", "arrow_sddmm_device_bytes",
+    "arrow_set_workspace", "arrow_spmm", "arrow_spmm_static", "arrow_spmm_iter", "arrow_sddmm_device_bytes",
     "arrow_sddmm_upload", "arrow_sddmm", "arrow_export_entry_map", "arrow_gather", "arrow_info",
     "arrow_level_info", "arrow_export_level", "arrow_self_check", "arrow_set_option", "arrow_set_profiling",
     "arrow_get_profile", "arrow_get_level_profile", "arrow_save", "arrow_load", "arrow_last_error",
@@ -90,6 +90,8 @@ def lib():
     L.arrow_set_workspace.argtypes = [vp, vp, sz]
     L.arrow_spmm.restype = ctypes.c_int
     L.arrow_spmm.argtypes = [vp, vp, vp, i32, vp]
+    L.arrow_spmm_static.restype = ctypes.c_int
+    L.arrow_spmm_static.argtypes = [vp, vp, vp, i32, vp]
     L.arrow_spmm_iter.restype = ctypes.c_int
     L.arrow_spmm_iter.argtypes = [vp, vp, i32, i32, vp]
     L.arrow_sddmm_device_bytes.restype = sz
@@ -192,6 +194,13 @@ def arrow_set_workspace(h: int, dev_ptr: int, nbytes: int) -> None:
 
 def arrow_spmm(h: int, x_ptr: int, y_ptr: int, k: int, stream: int = 0) -> None:
     _check(lib().arrow_spmm(h, x_ptr, y_ptr, k, stream))
+
+
+ARROW_STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def arrow_spmm_static(h: int, x_ptr: int, y_ptr: int, k: int, stream: int = 0) -> None:
+    _check(lib().arrow_spmm_static(h, x_ptr, y_ptr, k, stream))
 
 
 def arrow_spmm_iter(h: int, x_ptr: int, k: int, l: int, stream: int = 0) -> None:

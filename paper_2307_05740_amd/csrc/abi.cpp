@@ -10,6 +10,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -41,6 +42,36 @@ int64_t env_int(const char* name, int64_t dflt) {
 
 constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+// Scratch memory of arrow_spmm_static: one array per GPU the library is loaded on, held until the
+// process ends.  In host code the array's name is only a stand-in for the symbol; the device
+// address is looked up once per device (static_scratch) and that pointer is what kernels get.
+static __device__ __align__(256) unsigned char scratch[ARROW_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+// device address of the current device's scratch array (NULL + error text on failure)
+unsigned char* static_scratch() {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    g_err = std::string("static scratch: no usable current device: ") + hipGetErrorString(e);
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      g_err = std::string("static scratch: hipGetSymbolAddress failed: ") + hipGetErrorString(e);
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = static_cast<unsigned char*>(ptr);
+  }
+  return g_scratch_ptr[dev];
+}
 
 enum KernelClass { kRows = 0, kChunks = 1, kReduce = 2, kStage = 3, kWindow = 4, kPanel = 5, kClasses = 6 };
 
@@ -96,8 +127,8 @@ struct Scoped {
   arrow_handle* h;
   hipStream_t s;
   Span* sp = nullptr;
-  Scoped(arrow_handle* h_, int cls, int level, hipStream_t s_) : h(h_), s(s_) {
-    if (!h->profiling) return;
+  Scoped(arrow_handle* h_, int cls, int level, hipStream_t s_, bool allowed = true) : h(h_), s(s_) {
+    if (!h->profiling || !allowed) return;
     if (h->spans_used == h->spans.size()) {
       Span n{cls, level, nullptr, nullptr};
       if (hipEventCreate(&n.a) != hipSuccess || hipEventCreate(&n.b) != hipSuccess) return;
@@ -138,11 +169,15 @@ int check_hip(int rc, const char* what) {
   return fail(ARROW_EHIP, "%s: %s", what, hipGetErrorString((hipError_t)rc));
 }
 
-// one product, src -> dst (device, n x k), all levels in stream order
-int product(arrow_handle* h, const float* X, float* Y, int32_t k, hipStream_t stream) {
-  float* partials = reinterpret_cast<float*>(h->ws);
-  float* stage = reinterpret_cast<float*>(h->ws + partial_bytes(h, k));
-  float* panel_part = reinterpret_cast<float*>(h->ws + partial_bytes(h, k) + stage_bytes(h, k));
+// one product, src -> dst (device, n x k), all levels in stream order.  `ws` holds the partial
+// vectors, the staged head and the panel results (the caller's workspace, or the static scratch
+// array); every byte of it that a kernel reads has been written earlier in the same product.
+// prof = false: no event is created or recorded, whatever the handle's profiling switch says.
+int product(arrow_handle* h, const float* X, float* Y, int32_t k, hipStream_t stream,
+            unsigned char* ws, bool prof) {
+  float* partials = reinterpret_cast<float*>(ws);
+  float* stage = reinterpret_cast<float*>(ws + partial_bytes(h, k));
+  float* panel_part = reinterpret_cast<float*>(ws + partial_bytes(h, k) + stage_bytes(h, k));
   for (size_t li = 0; li < h->img.levels.size(); ++li) {
     const arrow::LevelImage& im = h->img.levels[li];
     const bool acc = li > 0;
@@ -151,7 +186,7 @@ int product(arrow_handle* h, const float* X, float* Y, int32_t k, hipStream_t st
     arrow::LaunchTuning tune = h->tuning;
     if (im.staged) {
       // the first-block-column window X_0 = (P_i X)[0:b], made contiguous once per product
-      Scoped sc(h, kStage, (int)li, stream);
+      Scoped sc(h, kStage, (int)li, stream, prof);
       int rc = arrow::launch_gather(at<int32_t>(h, im.off_stage_perm), im.n_stage, X, stage, k, stream);
       if (rc) return check_hip(rc, "head staging launch");
       Xh = stage;
@@ -169,14 +204,14 @@ int product(arrow_handle* h, const float* X, float* Y, int32_t k, hipStream_t st
       }
     }
     if (im.n_chunks > 0) {
-      Scoped sc(h, kChunks, (int)li, stream);
+      Scoped sc(h, kChunks, (int)li, stream, prof);
       int rc = arrow::launch_chunks(at<uint32_t>(h, im.off_chunk_ptr), at<uint32_t>(h, im.off_chunk_mid),
                                     at<int32_t>(h, im.off_chunk_dst), ent, im.n_chunks, X, h->n, Xh, Y,
                                     partials, k, acc, tune, stream);
       if (rc) return check_hip(rc, "chunks kernel launch");
     }
     if (im.n_rows > 0) {
-      Scoped sc(h, kRows, (int)li, stream);
+      Scoped sc(h, kRows, (int)li, stream, prof);
       // class pieces (die queues) follow the chunk kernel's column slicing; the short rows behind
       // them run in one pass over whole rows
       const int64_t np = im.piece_slots;
@@ -190,7 +225,7 @@ int product(arrow_handle* h, const float* X, float* Y, int32_t k, hipStream_t st
       if (rc) return check_hip(rc, "rows kernel launch");
     }
     if (im.n_wtiles > 0) {
-      Scoped sc(h, kWindow, (int)li, stream);
+      Scoped sc(h, kWindow, (int)li, stream, prof);
       int rc = arrow::launch_window(at<arrow::WindowTile>(h, im.off_wtiles), im.n_wtiles,
                                     h->img.max_window_span, at<uint32_t>(h, im.off_wrow_ptr),
                                     at<uint32_t>(h, im.off_wrow_mid), at<int32_t>(h, im.off_wrow_y), ent,
@@ -198,14 +233,14 @@ int product(arrow_handle* h, const float* X, float* Y, int32_t k, hipStream_t st
       if (rc) return check_hip(rc, "window kernel launch");
     }
     if (im.n_split > 0) {
-      Scoped sc(h, kReduce, (int)li, stream);
+      Scoped sc(h, kReduce, (int)li, stream, prof);
       int rc = arrow::launch_reduce(at<uint32_t>(h, im.off_split_ptr), at<int32_t>(h, im.off_split_y),
                                     im.n_split, partials, Y, k, acc, stream);
       if (rc) return check_hip(rc, "reduce kernel launch");
     }
     if (im.n_panel_groups > 0) {
       // last: the panels add to rows of Y the launches above have stored
-      Scoped sc(h, kPanel, (int)li, stream);
+      Scoped sc(h, kPanel, (int)li, stream, prof);
       int rc = arrow::launch_panel(at<uint32_t>(h, im.off_panel_ptr), at<int32_t>(h, im.off_panel_y), ent,
                                    im.n_panel_groups, Xh, im.n_stage, panel_part, k, stream);
       if (rc) return check_hip(rc, "panel kernel launch");
@@ -427,6 +462,9 @@ int arrow_upload(arrow_handle* h, void* dev_buf, size_t bytes, void* stream) {
     if (e != hipSuccess) return check_hip((int)e, "image upload");
   }
   h->dev = static_cast<unsigned char*>(dev_buf);
+  // set-up on this device: look up the address of its copy of the static scratch array, so that
+  // arrow_spmm_static never has to (a failure only matters to that call, which reports it)
+  (void)static_scratch();
   return ARROW_OK;
 }
 
@@ -451,7 +489,22 @@ int arrow_spmm(arrow_handle* h, const float* X, float* Y, int32_t k, void* strea
   rc = check_operands(h, X, Y, k, h->ws, h->ws_bytes);
   if (rc) return rc;
   h->spans_used = 0;
-  return product(h, X, Y, k, (hipStream_t)stream);
+  return product(h, X, Y, k, (hipStream_t)stream, h->ws, true);
+}
+
+int arrow_spmm_static(arrow_handle* h, const float* X, float* Y, int32_t k, void* stream) {
+  if (!h) return fail(ARROW_EINVAL, "handle is NULL");
+  if (k < 1) return fail(ARROW_EINVAL, "k must be >= 1 (got %d)", k);
+  if (!h->dev) return fail(ARROW_ENOTREADY, "arrow_upload has not been called");
+  const size_t need = partial_bytes(h, k) + stage_bytes(h, k) + panel_bytes(h, k);
+  if (need > (size_t)ARROW_STATIC_SCRATCH_BYTES)
+    return fail(ARROW_ETOOSMALL, "k = %d needs %zu bytes of scratch, the static array holds %zu; use "
+                "arrow_spmm with a workspace", k, need, (size_t)ARROW_STATIC_SCRATCH_BYTES);
+  int rc = check_operands(h, X, Y, k, nullptr, 0);
+  if (rc) return rc;
+  unsigned char* ws = static_scratch();   // resolved by arrow_upload on this device; a lookup, not an allocation
+  if (!ws) return ARROW_EHIP;
+  return product(h, X, Y, k, (hipStream_t)stream, ws, false);
 }
 
 int arrow_spmm_iter(arrow_handle* h, float* X, int32_t k, int32_t l, void* stream) {
@@ -469,7 +522,7 @@ int arrow_spmm_iter(arrow_handle* h, float* X, int32_t k, int32_t l, void* strea
   float* src = X;
   float* dst = tmp;
   for (int32_t t = 0; t < l; ++t) {
-    rc = product(h, src, dst, k, (hipStream_t)stream);
+    rc = product(h, src, dst, k, (hipStream_t)stream, h->ws, true);
     if (rc) return rc;
     float* s = src; src = dst; dst = s;
   }

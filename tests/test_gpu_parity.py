@@ -426,6 +426,9 @@ def test_errors_on_device(torch):
         with pytest.raises(binding.ArrowError) as ei:
             binding.arrow_spmm(op.h, x_ptr, y_ptr, 8, 0)
         assert ei.value.code == binding.ARROW_EINVAL and "overlap" in str(ei.value)
+    with pytest.raises(binding.ArrowError) as ei:
+        binding.arrow_spmm_static(op.h, big.data_ptr(), half, 8, 0)
+    assert ei.value.code == binding.ARROW_EINVAL
     with pytest.raises(binding.ArrowError) as ei:                     # workspace bound for k = 8 only
         binding.arrow_spmm_iter(op.h, Xd.data_ptr(), 64, 2, 0)
     assert ei.value.code == binding.ARROW_ETOOSMALL
