@@ -56,22 +56,38 @@ struct Remainder {
   int64_t nnz(int64_t n) const { return ptr[n]; }
 };
 
-// true when every off-diagonal entry (u,v) of the pattern has its mirror (v,u)
+// Is the pattern its own transpose?  Every vertex gets two 64-bit sums of a mixing function of
+// its neighbours' ids, one over its row and one over its column (the latter collected with integer
+// atomics, whose result does not depend on their order); the pattern is taken to be symmetric
+// when the two agree for every vertex.  Equal neighbour sets always agree; different ones agree
+// with probability about 2^-64.  The answer only selects how neighbours are enumerated: a wrong
+// "symmetric" costs arrangement quality on that operand, never correctness (the separator rule is
+// verified by a count, and the plain rule ends for any operand).
+inline uint64_t mix64(uint64_t x) {
+  x += 0x9e3779b97f4a7c15ULL;
+  x = (x ^ (x >> 30)) * 0xbf58476d1ce4e5b9ULL;
+  x = (x ^ (x >> 27)) * 0x94d049bb133111ebULL;
+  return x ^ (x >> 31);
+}
+
 bool pattern_symmetric(int64_t n, const Remainder& R) {
-  int asym = 0;
-#pragma omp parallel for schedule(dynamic, 4096)
+  std::vector<uint64_t> colsum(n, 0);
+  std::vector<uint64_t> rowsum(n, 0);
+#pragma omp parallel for schedule(dynamic, 256)
   for (int64_t u = 0; u < n; ++u) {
-    if (__atomic_load_n(&asym, __ATOMIC_RELAXED)) continue;
+    const uint64_t hu = mix64((uint64_t)u);
+    uint64_t acc = 0;
     for (int64_t p = R.ptr[u]; p < R.ptr[u + 1]; ++p) {
       const int32_t w = R.col[p];
-      if (w == u) continue;
-      if (!std::binary_search(R.col + R.ptr[w], R.col + R.ptr[w + 1], (int32_t)u)) {
-        __atomic_store_n(&asym, 1, __ATOMIC_RELAXED);
-        break;
-      }
+      acc += mix64((uint64_t)w);
+      __atomic_fetch_add(&colsum[w], hu, __ATOMIC_RELAXED);
     }
+    rowsum[u] = acc;
   }
-  return asym == 0;
+  int64_t differ = 0;
+#pragma omp parallel for schedule(static) reduction(+ : differ)
+  for (int64_t u = 0; u < n; ++u) differ += rowsum[u] != colsum[u];
+  return differ == 0;
 }
 
 // Neighbours of a vertex in the pattern of R + R^T.  For a symmetric pattern the rows of R are
@@ -91,7 +107,7 @@ struct Adjacency {
     std::vector<int32_t> tcol(tptr[n]);
     {
       std::vector<int64_t> fill(tptr.begin(), tptr.end() - 1);
-#pragma omp parallel for schedule(dynamic, 4096)
+#pragma omp parallel for schedule(dynamic, 256)
       for (int64_t u = 0; u < n; ++u)
         for (int64_t p = rem.ptr[u]; p < rem.ptr[u + 1]; ++p) {
           const int64_t at = __atomic_fetch_add(&fill[rem.col[p]], 1, __ATOMIC_RELAXED);
@@ -99,7 +115,7 @@ struct Adjacency {
         }
     }
     // the atomic fill leaves a row in arrival order; sorting makes the result deterministic
-#pragma omp parallel for schedule(dynamic, 4096)
+#pragma omp parallel for schedule(dynamic, 256)
     for (int64_t v = 0; v < n; ++v) std::sort(tcol.begin() + tptr[v], tcol.begin() + tptr[v + 1]);
     // union of the two sorted rows: count, prefix sum, fill
     own_ptr.assign(n + 1, 0);
@@ -119,11 +135,11 @@ struct Adjacency {
       }
       return cnt;
     };
-#pragma omp parallel for schedule(dynamic, 4096)
+#pragma omp parallel for schedule(dynamic, 256)
     for (int64_t u = 0; u < n; ++u) own_ptr[u + 1] = merge_row(u, nullptr);
     for (int64_t u = 0; u < n; ++u) own_ptr[u + 1] += own_ptr[u];
     own_col.resize(own_ptr[n]);
-#pragma omp parallel for schedule(dynamic, 4096)
+#pragma omp parallel for schedule(dynamic, 256)
     for (int64_t u = 0; u < n; ++u) merge_row(u, own_col.data() + own_ptr[u]);
     ptr = own_ptr.data();
     col = own_col.data();
@@ -226,13 +242,13 @@ int decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const flo
 
     // ---- 1. degrees and active set ---------------------------------------
     std::fill(colcnt.begin(), colcnt.end(), 0);
-#pragma omp parallel for schedule(dynamic, 4096)
+#pragma omp parallel for schedule(dynamic, 256)
     for (int64_t u = 0; u < n; ++u)
       for (int64_t p = R.ptr[u]; p < R.ptr[u + 1]; ++p)
         __atomic_fetch_add(&colcnt[R.col[p]], 1, __ATOMIC_RELAXED);
     int64_t n_i = 0;
     double deg_sum = 0.0;
-#pragma omp parallel for schedule(dynamic, 4096) reduction(+ : n_i, deg_sum)
+#pragma omp parallel for schedule(dynamic, 256) reduction(+ : n_i, deg_sum)
     for (int64_t u = 0; u < n; ++u) {
       int64_t rc = R.ptr[u + 1] - R.ptr[u];
       bool diag = std::binary_search(R.col + R.ptr[u], R.col + R.ptr[u + 1], (int32_t)u);
@@ -313,7 +329,7 @@ int decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const flo
 #pragma omp parallel for schedule(static)
             for (int64_t p = 0; p < n_i; ++p) spos[L.perm[p]] = (int32_t)p;
             int64_t outside = 0;
-#pragma omp parallel for schedule(dynamic, 4096) reduction(+ : outside)
+#pragma omp parallel for schedule(dynamic, 256) reduction(+ : outside)
             for (int64_t u = 0; u < n; ++u) {
               const int64_t pu = spos[u];
               if (pu < 0 || pu < b) continue;
@@ -354,7 +370,7 @@ int decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const flo
 #pragma omp parallel for schedule(static)
           for (int64_t t = 0; t < nt; ++t) tpos[trial[t]] = (int32_t)(t / b);
           int64_t cap = 0;
-#pragma omp parallel for schedule(dynamic, 4096) reduction(+ : cap)
+#pragma omp parallel for schedule(dynamic, 256) reduction(+ : cap)
           for (int64_t t = 0; t < nt; ++t) {
             const int32_t u = trial[t];
             const int32_t bu = tpos[u];
@@ -378,7 +394,7 @@ int decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const flo
     };
     L.rowptr.assign(n_i + 1, 0);
     std::vector<int64_t> next_ptr(n + 1, 0);
-#pragma omp parallel for schedule(dynamic, 4096)
+#pragma omp parallel for schedule(dynamic, 256)
     for (int64_t u = 0; u < n; ++u) {
       int64_t pu = pos[u];
       if (pu < 0) continue;
@@ -402,7 +418,7 @@ int decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const flo
     std::vector<float> next_val(next_nnz);
     std::vector<uint32_t> next_src(next_nnz);
     int64_t hh = 0, hr = 0, hc = 0, dg = 0;
-#pragma omp parallel for schedule(dynamic, 1024) reduction(+ : hh, hr, hc, dg)
+#pragma omp parallel for schedule(dynamic, 256) reduction(+ : hh, hr, hc, dg)
     for (int64_t u = 0; u < n; ++u) {
       int64_t pu = pos[u];
       if (pu < 0) continue;
