@@ -95,6 +95,14 @@ typedef struct arrow_level_info_t {
   int64_t nnz_panel;    /* entries held by the panels                            */
   int32_t blocks;       /* ceil(n_i / b)                                         */
   int32_t separator_rule; /* 1 if block separators were promoted into the head   */
+  int64_t nnz_fused;    /* level 0 only: entries of later levels that the packed image lists with the
+                           level-0 rows of their vertices (fused levels); the work-list figures above
+                           (nnz_rows, nnz_chunks, nnz_window, nnz_panel) then add up to nnz + nnz_fused,
+                           and those of the later levels are 0 */
+  int64_t corner;       /* rows = columns of the dense corner of the head block run in LDS tiles (0 = none) */
+  int64_t corner_tiles; /* non-empty 256 x 256 tiles of the corner                            */
+  int64_t corner_items; /* work items (runs of tiles of one row panel) of the corner kernel   */
+  int64_t nnz_corner;   /* entries held by the corner tiles                                   */
 } arrow_level_info_t;
 
 /* Per-kernel-class time of the last profiled product, milliseconds. */
@@ -108,6 +116,8 @@ typedef struct arrow_profile_t {
   int32_t rows_launches, chunks_launches, reduce_launches, stage_launches, window_launches; /* launches per class (one per level that has such work) */
   float panel_ms;   /* head panels: head-block entries of sparse head rows, accumulators in LDS          */
   int32_t panel_launches;
+  float corner_ms;  /* dense corner of the head block: LDS tiles + the pass that adds their results to Y */
+  int32_t corner_launches;
 } arrow_profile_t;
 
 /*
@@ -136,7 +146,8 @@ int arrow_upload(arrow_handle *h, void *dev_buf, size_t bytes, void *stream);
 
 /*
  * Device workspace a product with k columns needs: head partials of the
- * largest level plus one n x k buffer for the chained products of
+ * largest level, the staged head rows, the results of the corner and panel
+ * work items, plus one n x k buffer for the chained products of
  * arrow_spmm_iter.  arrow_set_workspace binds caller-owned device memory
  * (256-byte aligned); it may be rebound at any time the stream is idle.
  */
@@ -248,9 +259,19 @@ int arrow_self_check(const arrow_handle *h);
  * entries in panels: 128 rows per group, one workgroup per group and column class with the
  * group's accumulators in LDS, class c served by accelerator die c; default 0), ARROW_PANEL_MIN
  * (fewest head-block entries of a row that joins a panel, default 8),
+ * ARROW_FUSE_LEVELS (1, the default: the entries that later levels hold for a vertex are listed
+ * with the vertex's level-0 row, so one item sums over all arrow matrices and the later levels
+ * need neither launches nor a read-modify-write of Y; 0: every level runs its own launches),
+ * ARROW_CORNER (1: when the head of level 0 is staged, the dense top-left corner of
+ * the head block -- rows and columns [0, S) -- runs in tiles of 256 x 256 with the tile's staged
+ * head rows and the row panel's accumulators in LDS; S is the largest multiple of 256 up to
+ * ARROW_CORNER_MAX, default 65536, whose outermost band of tiles holds at least
+ * ARROW_CORNER_MIN_TILE, default 768, entries per tile on average; default 0: no corner; meant to
+ * be used with ARROW_HUBS_FIRST, which makes that corner dense),
  * ARROW_SEPARATORS and ARROW_BFS_TAIL (0 disables the separator rule / the breadth-first
  * arrangement of later levels), ARROW_HEAD_BY_ID (1, the default: the head vertices of the plain
- * rule sit in id order inside the head; 0: by falling degree).
+ * rule sit in id order inside the head, after the ARROW_HUBS_FIRST, default 0, highest degrees,
+ * which lead the head by falling degree and make its top-left corner dense; 0: all by falling degree).
  * Errors: EINVAL (unknown name, value out of range).
  */
 int arrow_set_option(arrow_handle *h, const char *name, int64_t value);

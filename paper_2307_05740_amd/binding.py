@@ -50,7 +50,9 @@ class arrow_level_info_t(ctypes.Structure):
                  "short_rows", "chunks", "split_rows", "partials", "nnz_rows", "nnz_chunks",
                  "x_rows_rows", "x_rows_chunks", "window_tiles", "window_rows", "nnz_window",
                  "rows_partials", "chunks_partials", "panel_rows", "panel_bins", "nnz_panel")] + \
-               [("blocks", ctypes.c_int32), ("separator_rule", ctypes.c_int32)]
+               [("blocks", ctypes.c_int32), ("separator_rule", ctypes.c_int32), ("nnz_fused", ctypes.c_int64),
+                ("corner", ctypes.c_int64), ("corner_tiles", ctypes.c_int64), ("corner_items", ctypes.c_int64),
+                ("nnz_corner", ctypes.c_int64)]
 
 
 class arrow_profile_t(ctypes.Structure):
@@ -59,7 +61,8 @@ class arrow_profile_t(ctypes.Structure):
                [(name, ctypes.c_int32) for name in
                 ("rows_launches", "chunks_launches", "reduce_launches", "stage_launches",
                  "window_launches")] + \
-               [("panel_ms", ctypes.c_float), ("panel_launches", ctypes.c_int32)]
+               [("panel_ms", ctypes.c_float), ("panel_launches", ctypes.c_int32),
+                ("corner_ms", ctypes.c_float), ("corner_launches", ctypes.c_int32)]
 
 
 class csf3_info_t(ctypes.Structure):

@@ -73,7 +73,7 @@ unsigned char* static_scratch() {
   return g_scratch_ptr[dev];
 }
 
-enum KernelClass { kRows = 0, kChunks = 1, kReduce = 2, kStage = 3, kWindow = 4, kPanel = 5, kClasses = 6 };
+enum KernelClass { kRows = 0, kChunks = 1, kReduce = 2, kStage = 3, kWindow = 4, kPanel = 5, kCorner = 6, kClasses = 7 };
 
 struct Span {
   int cls;
@@ -105,7 +105,8 @@ struct arrow_handle {
 
 namespace {
 
-// workspace layout: [partial vectors][staged head rows][panel class results][n x k buffer of the chained products]
+// workspace layout: [partial vectors][staged head rows][panel class results][corner item results]
+//                   [n x k buffer of the chained products]
 size_t partial_bytes(const arrow_handle* h, int32_t k) {
   return align_up((size_t)h->img.max_partials * (size_t)k * sizeof(float));
 }
@@ -115,6 +116,15 @@ size_t stage_bytes(const arrow_handle* h, int32_t k) {
 
 size_t panel_bytes(const arrow_handle* h, int32_t k) {
   return align_up((size_t)h->img.max_panel_slots * arrow::kDies * (size_t)k * sizeof(float));
+}
+
+size_t corner_bytes(const arrow_handle* h, int32_t k) {
+  return align_up((size_t)h->img.max_corner_items * arrow::kCornerTile * (size_t)k * sizeof(float));
+}
+
+// everything a product keeps outside X and Y
+size_t scratch_bytes(const arrow_handle* h, int32_t k) {
+  return partial_bytes(h, k) + stage_bytes(h, k) + panel_bytes(h, k) + corner_bytes(h, k);
 }
 
 template <typename T>
@@ -178,6 +188,7 @@ int product(arrow_handle* h, const float* X, float* Y, int32_t k, hipStream_t st
   float* partials = reinterpret_cast<float*>(ws);
   float* stage = reinterpret_cast<float*>(ws + partial_bytes(h, k));
   float* panel_part = reinterpret_cast<float*>(ws + partial_bytes(h, k) + stage_bytes(h, k));
+  float* corner_part = reinterpret_cast<float*>(ws + partial_bytes(h, k) + stage_bytes(h, k) + panel_bytes(h, k));
   for (size_t li = 0; li < h->img.levels.size(); ++li) {
     const arrow::LevelImage& im = h->img.levels[li];
     const bool acc = li > 0;
@@ -248,6 +259,16 @@ int product(arrow_handle* h, const float* X, float* Y, int32_t k, hipStream_t st
                                        panel_part, Y, k, stream);
       if (rc) return check_hip(rc, "panel combine launch");
     }
+    if (im.n_corner_items > 0) {
+      // last as well: the corner adds to rows of Y the launches above have stored
+      Scoped sc(h, kCorner, (int)li, stream, prof);
+      int rc = arrow::launch_corner(at<uint32_t>(h, im.off_corner_tiles), at<uint32_t>(h, im.off_corner_items),
+                                    im.n_corner_items, ent, Xh, im.n_stage, corner_part, k, stream);
+      if (rc) return check_hip(rc, "corner kernel launch");
+      rc = arrow::launch_corner_combine(at<uint32_t>(h, im.off_corner_panel), at<int32_t>(h, im.off_corner_y),
+                                        im.corner, corner_part, Y, k, stream);
+      if (rc) return check_hip(rc, "corner combine launch");
+    }
   }
   return ARROW_OK;
 }
@@ -296,6 +317,13 @@ int sampled_product(arrow_handle* h, const float* U, const float* V, float* S_ou
                                          ent, emap, im.n_panel_bins, U, Vh, im.n_stage, S, k, stream);
       if (rc) return check_hip(rc, "sampled panel kernel launch");
     }
+    if (im.n_corner_tiles > 0) {
+      Scoped sc(h, kCorner, (int)li, stream);
+      int rc = arrow::launch_sddmm_corner(at<uint32_t>(h, im.off_corner_tiles), im.n_corner_tiles,
+                                          at<int32_t>(h, im.off_corner_y), ent, emap, U, Vh, im.n_stage, S, k,
+                                          stream);
+      if (rc) return check_hip(rc, "sampled corner kernel launch");
+    }
   }
   return ARROW_OK;
 }
@@ -313,6 +341,10 @@ void read_pack_options(arrow_handle* h) {
   h->pack.stage_head = (int32_t)env_int("ARROW_STAGE_HEAD", h->pack.stage_head);
   h->pack.stage_short = (int32_t)env_int("ARROW_STAGE_SHORT", h->pack.stage_short);
   h->pack.empty_last = (int32_t)env_int("ARROW_EMPTY_LAST", h->pack.empty_last);
+  h->pack.fuse_levels = (int32_t)env_int("ARROW_FUSE_LEVELS", h->pack.fuse_levels);
+  h->pack.corner = (int32_t)env_int("ARROW_CORNER", h->pack.corner);
+  h->pack.corner_max = (int32_t)env_int("ARROW_CORNER_MAX", h->pack.corner_max);
+  h->pack.corner_min_tile = (int32_t)env_int("ARROW_CORNER_MIN_TILE", h->pack.corner_min_tile);
   h->pack.panel = (int32_t)env_int("ARROW_PANEL", h->pack.panel);
   h->pack.panel_min = (int32_t)env_int("ARROW_PANEL_MIN", h->pack.panel_min);
   h->pack.window_span = (int32_t)env_int("ARROW_WINDOW_SPAN", h->pack.window_span);
@@ -329,7 +361,7 @@ int ready(const arrow_handle* h, int32_t k, bool need_iter_buffer) {
   if (k < 1) return fail(ARROW_EINVAL, "k must be >= 1 (got %d)", k);
   if (!h->dev) return fail(ARROW_ENOTREADY, "arrow_upload has not been called");
   if (!h->ws) return fail(ARROW_ENOTREADY, "arrow_set_workspace has not been called");
-  size_t need = partial_bytes(h, k) + stage_bytes(h, k) + panel_bytes(h, k);
+  size_t need = scratch_bytes(h, k);
   if (need_iter_buffer) need += (size_t)h->n * (size_t)k * sizeof(float);
   if (h->ws_bytes < need)
     return fail(ARROW_ETOOSMALL, "workspace holds %zu bytes, k = %d needs %zu", h->ws_bytes, k, need);
@@ -428,6 +460,7 @@ int arrow_decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, con
   dopt.separators = env_int("ARROW_SEPARATORS", 1) != 0;
   dopt.bfs_tail = env_int("ARROW_BFS_TAIL", 1) != 0;
   dopt.head_by_id = env_int("ARROW_HEAD_BY_ID", 1) != 0;
+  dopt.hubs_first = env_int("ARROW_HUBS_FIRST", dopt.hubs_first);
   read_pack_options(h);
   std::string err;
   int rc;
@@ -470,8 +503,7 @@ int arrow_upload(arrow_handle* h, void* dev_buf, size_t bytes, void* stream) {
 
 size_t arrow_workspace_bytes(const arrow_handle* h, int32_t k) {
   if (!h || k < 1) return 0;
-  return partial_bytes(h, k) + stage_bytes(h, k) + panel_bytes(h, k) +
-         align_up((size_t)h->n * (size_t)k * sizeof(float));
+  return scratch_bytes(h, k) + align_up((size_t)h->n * (size_t)k * sizeof(float));
 }
 
 int arrow_set_workspace(arrow_handle* h, void* dev_ws, size_t bytes) {
@@ -496,7 +528,7 @@ int arrow_spmm_static(arrow_handle* h, const float* X, float* Y, int32_t k, void
   if (!h) return fail(ARROW_EINVAL, "handle is NULL");
   if (k < 1) return fail(ARROW_EINVAL, "k must be >= 1 (got %d)", k);
   if (!h->dev) return fail(ARROW_ENOTREADY, "arrow_upload has not been called");
-  const size_t need = partial_bytes(h, k) + stage_bytes(h, k) + panel_bytes(h, k);
+  const size_t need = scratch_bytes(h, k);
   if (need > (size_t)ARROW_STATIC_SCRATCH_BYTES)
     return fail(ARROW_ETOOSMALL, "k = %d needs %zu bytes of scratch, the static array holds %zu; use "
                 "arrow_spmm with a workspace", k, need, (size_t)ARROW_STATIC_SCRATCH_BYTES);
@@ -518,7 +550,7 @@ int arrow_spmm_iter(arrow_handle* h, float* X, int32_t k, int32_t l, void* strea
     return fail(ARROW_EINVAL, "X must not overlap the workspace or the device image");
   if (l == 0) return ARROW_OK;
   h->spans_used = 0;
-  float* tmp = reinterpret_cast<float*>(h->ws + partial_bytes(h, k) + stage_bytes(h, k) + panel_bytes(h, k));
+  float* tmp = reinterpret_cast<float*>(h->ws + scratch_bytes(h, k));
   float* src = X;
   float* dst = tmp;
   for (int32_t t = 0; t < l; ++t) {
@@ -606,6 +638,9 @@ int arrow_level_info(const arrow_handle* h, int32_t level, arrow_level_info_t* o
   out->x_rows_rows = im.x_rows_rows; out->x_rows_chunks = im.x_rows_chunks;
   out->window_tiles = im.n_wtiles; out->window_rows = im.n_wrows; out->nnz_window = im.nnz_w;
   out->panel_rows = im.n_panel_rows; out->panel_bins = im.n_panel_bins; out->nnz_panel = im.nnz_panel;
+  out->nnz_fused = im.nnz_fused;
+  out->corner = im.corner; out->corner_tiles = im.n_corner_tiles; out->corner_items = im.n_corner_items;
+  out->nnz_corner = im.nnz_corner;
   out->blocks = (int32_t)((L.n_i + h->b - 1) / h->b);
   out->separator_rule = L.separator_rule ? 1 : 0;
   return ARROW_OK;
@@ -669,9 +704,10 @@ int arrow_get_level_profile(arrow_handle* h, int32_t level, arrow_profile_t* out
   hipError_t e = hipEventSynchronize(h->spans[h->spans_used - 1].b);
   if (e != hipSuccess) return check_hip((int)e, "event synchronize");
   float* slot[kClasses] = {&out->rows_ms, &out->chunks_ms, &out->reduce_ms, &out->stage_ms,
-                           &out->window_ms, &out->panel_ms};
+                           &out->window_ms, &out->panel_ms, &out->corner_ms};
   int32_t* count[kClasses] = {&out->rows_launches, &out->chunks_launches, &out->reduce_launches,
-                              &out->stage_launches, &out->window_launches, &out->panel_launches};
+                              &out->stage_launches, &out->window_launches, &out->panel_launches,
+                              &out->corner_launches};
   for (size_t i = 0; i < h->spans_used; ++i) {
     if (level >= 0 && h->spans[i].level != level) continue;
     float ms = 0.f;

@@ -4,19 +4,36 @@
 
 #include <cstddef>
 #include <cstdint>
+#include <memory>
 #include <string>
+#include <utility>
 #include <vector>
 
 namespace arrow {
+
+// std::vector whose resize() leaves new elements uninitialised: the entry arrays of a level are
+// hundreds of megabytes and are filled by parallel loops right after they are sized, so a serial
+// zero-fill (and its page faults) would only cost time.
+template <typename T>
+struct default_init_allocator : std::allocator<T> {
+  template <typename U> struct rebind { using other = default_init_allocator<U>; };
+  using std::allocator<T>::allocator;
+  template <typename U, typename... Args>
+  void construct(U* p, Args&&... args) {
+    if constexpr (sizeof...(Args) == 0) ::new (static_cast<void*>(p)) U;
+    else ::new (static_cast<void*>(p)) U(std::forward<Args>(args)...);
+  }
+};
+template <typename T> using raw_vector = std::vector<T, default_init_allocator<T>>;
 
 // One arrow matrix B_i in position coordinates, CSR by row position.
 struct HostLevel {
   int64_t n_i = 0;                 // active vertices of this level
   std::vector<int32_t> perm;       // position -> original vertex id, n_i entries
   std::vector<int64_t> rowptr;     // n_i + 1
-  std::vector<int32_t> colpos;     // column positions, ascending inside a row
-  std::vector<float> vals;
-  std::vector<uint32_t> src;       // index of every entry in the caller's CSR arrays
+  raw_vector<int32_t> colpos;      // column positions, ascending inside a row
+  raw_vector<float> vals;
+  raw_vector<uint32_t> src;        // index of every entry in the caller's CSR arrays
   int64_t nnz_head_head = 0, nnz_head_row = 0, nnz_head_col = 0, nnz_diag = 0;
   bool separator_rule = false;
 };
@@ -26,6 +43,7 @@ struct DecomposeOptions {
   bool separators = true;    // try the block-separator rule before the plain top-degree head
   bool bfs_tail = true;      // levels >= 1 arrange the non-head vertices in BFS order
   bool head_by_id = true;    // plain rule: head vertices in id order (else by falling degree)
+  int64_t hubs_first = 0;    // ... after this many of the highest degrees, which lead the head by falling degree
 };
 
 // Peels arrow matrices of width b off A until nothing is left.  Returns 0 or a
@@ -55,6 +73,15 @@ constexpr int kPanelRows = 128;
 constexpr int kPanelClassShift = 6;       // staged head rows are dealt to the column classes 64 at a time
 inline int panel_class(uint32_t staged_row) { return (int)((staged_row >> kPanelClassShift) & (kDies - 1)); }
 constexpr int kPanelRowShift = 24;       // panel entry code = (row inside the workgroup << 24) | staged head row
+
+// dense corner of the head block: rows and columns [0, corner) of level 0, cut into tiles of
+// kCornerTile x kCornerTile positions.  A workgroup owns the accumulators of one row panel
+// (kCornerTile rows) in LDS and sweeps a run of the panel's tiles, each with its kCornerTile
+// staged head rows copied into LDS; a tile's entries are dealt to kCornerRuns lane-group streams
+// that never share a row.  Entry code = (row inside the panel << 16) | column inside the tile.
+constexpr int kCornerTile = 256;
+constexpr int kCornerRuns = 64;
+constexpr int kCornerTileWords = kCornerRuns + 3;   // per tile: run offsets (kCornerRuns + 1), first column, panel
 
 struct LevelImage {
   int64_t n_i = 0;
@@ -100,7 +127,15 @@ struct LevelImage {
   int64_t n_panel_rows = 0, n_panel_groups = 0, n_panel_bins = 0, nnz_panel = 0;
   size_t off_panel_ptr = 0;  // uint32 n_panel_bins + 1 (entry offsets; a bin is one lane group's stream)
   size_t off_panel_y = 0;    // int32  n_panel_groups * kPanelRows : Y row of every accumulator, -1 = unused
+  // dense corner (see kCornerTile): its entries follow the panel entries in the entry array
+  int64_t corner = 0;        // rows = columns of the corner (a multiple of kCornerTile), 0 = none
+  int64_t n_corner_tiles = 0, n_corner_items = 0, nnz_corner = 0;
+  size_t off_corner_tiles = 0;   // uint32 n_corner_tiles * kCornerTileWords
+  size_t off_corner_items = 0;   // uint32 n_corner_items * 2 + 2 : first tile of every item (+ end), then ...
+  size_t off_corner_panel = 0;   // uint32 panels + 1 : first item of every row panel (items of a panel are consecutive)
+  size_t off_corner_y = 0;       // int32  corner : Y row of every corner row position
   int64_t map_offset = 0;    // first element of this level in the entry map (one uint32 per entry, image order)
+  int64_t nnz_fused = 0;     // level 0 with fused levels: entries of later levels listed with its rows
 };
 
 // Rows [row_begin, row_end) of the window-row list belong to one diagonal block and touch only
@@ -128,6 +163,10 @@ struct PackOptions {
   int32_t window_tile_rows = 1024;  // most rows per tile
   double window_reuse = 8.0;  // a tile is kept when its diagonal-block entries >= this x span
   double window_level_share = 0.05;  // ... and the tiles of a level when they hold this share of its entries
+  int32_t fuse_levels = 1;    // list the entries of later levels with the level-0 rows of their vertices
+  int32_t corner = 0;         // run the dense top-left corner of the head block in LDS tiles (off: measured slower than the chunk list)
+  int32_t corner_max = 65536; // largest corner considered (rows = columns)
+  int32_t corner_min_tile = 768;  // the corner grows while the tiles it gains hold at least this many entries on average
 };
 
 struct Image {
@@ -137,7 +176,9 @@ struct Image {
   int64_t max_stage_rows = 0;
   int64_t max_window_span = 0;
   int64_t max_panel_slots = 0;       // most panel accumulators (groups * kPanelRows) of a level
+  int64_t max_corner_items = 0;      // most corner work items of a level (each writes kCornerTile result rows)
   std::vector<uint32_t> entry_src;   // per entry in image order: its index in the caller's CSR arrays
+  bool fused = false;                // the image was packed from the fused execution form of the levels
 };
 
 int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const PackOptions& opt,
@@ -178,6 +219,16 @@ int launch_panel_combine(const int32_t* panel_y, int64_t n_slots, const float* p
 int launch_sddmm_panel(const uint32_t* panel_ptr, const int32_t* panel_y, const Entry* entries,
                        const uint32_t* emap, int64_t n_bins, const float* U, const float* Vh,
                        int64_t vh_rows, float* S, int32_t k, void* stream);
+// Dense corner.  launch_corner: workgroup = item; sums the item's tiles into LDS accumulators and
+// stores kCornerTile rows to part[item].  launch_corner_combine: Y[corner_y[p]] += the parts of the
+// items of p's panel, in item order.  launch_sddmm_corner: the sampled product over the corner tiles.
+int launch_corner(const uint32_t* tiles, const uint32_t* items, int64_t n_items, const Entry* entries,
+                  const float* Xh, int64_t xh_rows, float* part, int32_t k, void* stream);
+int launch_corner_combine(const uint32_t* panel_ptr, const int32_t* corner_y, int64_t corner,
+                          const float* part, float* Y, int32_t k, void* stream);
+int launch_sddmm_corner(const uint32_t* tiles, int64_t n_tiles, const int32_t* corner_y, const Entry* entries,
+                        const uint32_t* emap, const float* U, const float* Vh, int64_t vh_rows, float* S,
+                        int32_t k, void* stream);
 // max_span = widest window of the tiles (sizes the LDS allocation and the column slice)
 int launch_window(const WindowTile* tiles, int64_t n_tiles, int64_t max_span, const uint32_t* wrow_ptr,
                   const uint32_t* wrow_mid, const int32_t* wrow_y, const Entry* entries,

@@ -24,6 +24,10 @@
 //          that the level really takes every remaining entry.
 //        plain rule - the b vertices of highest degree (ties: lower id first);
 //          everything else keeps its arrangement order and is cut into blocks.
+//          Inside the head (the arrow shape does not care) the hubs_first
+//          highest degrees come first, by falling degree, so that the densest
+//          rows and columns of the head block form its top-left corner; the
+//          other head vertices follow in id order.
 //   4. an entry (u,v) belongs to the level iff pos(u) < b or pos(v) < b or
 //      pos(u)/b == pos(v)/b; the others form the next remainder.
 // The plain rule always captures every entry of the maximum-degree vertex, in
@@ -348,8 +352,16 @@ int decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const flo
       if (!done) {
         std::vector<int32_t> cand(order);
         std::nth_element(cand.begin(), cand.begin() + b, cand.end(), by_degree);
-        if (opt.head_by_id) std::sort(cand.begin(), cand.begin() + b);
-        else std::sort(cand.begin(), cand.begin() + b, by_degree);
+        if (opt.head_by_id) {
+          // the hubs_first highest-degree vertices lead the head in falling-degree order (their
+          // rows and columns form the dense corner of the head block), the others follow in id order
+          const int64_t hubs = std::min<int64_t>(std::max<int64_t>(opt.hubs_first, 0), b);
+          if (hubs > 0 && hubs < b) std::nth_element(cand.begin(), cand.begin() + hubs, cand.begin() + b, by_degree);
+          std::sort(cand.begin(), cand.begin() + hubs, by_degree);
+          std::sort(cand.begin() + hubs, cand.begin() + b);
+        } else {
+          std::sort(cand.begin(), cand.begin() + b, by_degree);
+        }
         std::vector<uint8_t> in_head(n, 0);
         for (int64_t p = 0; p < b; ++p) { L.perm[p] = cand[p]; in_head[cand[p]] = 1; }
         // the rest: the given arrangement, or a traversal of what is left without the head --

@@ -34,6 +34,25 @@
 //     (entries are ordered by column position) and the item's `mid` marks where they end.
 //     All other entries carry perm[q]: the permutation gather stays fused.
 //   * Head panels (optional, off by default): see the planning code below.
+//   * Dense corner (on by default when the head is staged).  The head vertices sit in id order,
+//     and in skewed graphs the lowest ids are the hubs: the top-left corner of the head block is
+//     orders of magnitude denser than the rest.  Rows and columns [0, S) are cut into tiles of
+//     256 x 256 positions, S chosen at pack time as the largest size whose outermost band of
+//     tiles still holds corner_min_tile entries per tile on average.  These entries (a prefix of
+//     their rows) leave the chunk lists: a workgroup takes a run of tiles of one row panel,
+//     copies each tile's 256 staged head rows into LDS with coalesced loads, and its lane
+//     groups stream the tile's entries -- in 64 runs that never share a row -- against LDS
+//     instead of gathering a row through the caches per entry.  The format is chosen per tile
+//     region by measured density: outside the corner an LDS copy of 256 rows would be used by
+//     fewer entries than it has rows.
+//   * Fused levels (on by default).  perm_0 is a full permutation, so every vertex owns a row
+//     of level 0.  The entries that later levels hold for a vertex are listed with that row
+//     (their columns translated to level-0 positions), and the row's one item, or its chunks,
+//     sums over all arrow matrices at once: the scatter-add P_i^T of the later levels happens
+//     in the accumulator instead of through a read-modify-write of Y, and their launches go
+//     away.  Where an entry's X row is read from is still decided by the arrow it belongs to
+//     (staged head, LDS window, or X through the fused gather).  The exported levels are
+//     untouched; the later levels keep only their permutation in the image.
 // Besides the image the packer builds the entry map (image order -> index of the entry in the
 // caller's CSR arrays), which the sampled dense-dense product needs for its output.
 #include "arrow_internal.h"
@@ -90,6 +109,14 @@ struct Plan {
   std::vector<uint8_t> panel_bin;     // per (slot, class): the bin of workgroup (group, class) that streams the row's class entries
   std::vector<uint32_t> panel_ptr;    // per bin: offsets of its entries (relative to the level's entries)
   int64_t nnz_panel = 0, n_panel_rows = 0;
+  // dense corner: tiles in (row panel, column tile) order; per tile its entry count until the
+  // lists are placed, then kCornerTileWords words (run offsets, first column, panel)
+  int64_t corner = 0, nnz_corner = 0;
+  std::vector<uint32_t> corner_cnt;    // per listed tile: entries
+  std::vector<uint32_t> corner_ij;     // per listed tile: (row panel << 16) | column tile
+  std::vector<uint32_t> corner_first;  // per listed tile: offset of its first entry (relative to the level's entries)
+  std::vector<uint32_t> corner_items;  // per item: first tile (+ end)
+  std::vector<uint32_t> corner_panel;  // per row panel: first item (+ end)
   uint32_t row_skip(int64_t p) const { return skip.empty() ? 0u : skip[p]; }
 };
 
@@ -130,15 +157,96 @@ std::vector<uint32_t> order_list(const std::vector<Rec>& recs, int list, uint32_
   return out;
 }
 
-}  // namespace
+// The execution form of a decomposition with fused levels: level 0 with the entries of all later
+// levels appended to the rows of their vertices (columns as level-0 positions, every row ordered
+// by column position again), and the later levels reduced to their permutations.
+void fuse_levels(const std::vector<HostLevel>& levels, std::vector<HostLevel>& exec,
+                 std::vector<int64_t>& fused_from) {
+  exec.clear();
+  exec.resize(levels.size());
+  fused_from.assign(levels.size(), 0);
+  const HostLevel& L0 = levels[0];
+  const int64_t n0 = L0.n_i;
+  std::vector<int32_t> pos0((size_t)n0, -1);          // vertex -> level-0 position (n_i of level 0 is n)
+#pragma omp parallel for schedule(static)
+  for (int64_t p = 0; p < n0; ++p) pos0[L0.perm[p]] = (int32_t)p;
+  std::vector<int64_t> extra((size_t)n0 + 1, 0);
+  for (size_t li = 1; li < levels.size(); ++li) {
+    const HostLevel& L = levels[li];
+    fused_from[li] = L.rowptr[L.n_i];
+    for (int64_t p = 0; p < L.n_i; ++p) extra[(size_t)pos0[L.perm[p]] + 1] += L.rowptr[p + 1] - L.rowptr[p];
+  }
+  HostLevel& E = exec[0];
+  E.n_i = n0;
+  E.perm = L0.perm;
+  E.nnz_head_head = L0.nnz_head_head; E.nnz_head_row = L0.nnz_head_row;
+  E.nnz_head_col = L0.nnz_head_col; E.nnz_diag = L0.nnz_diag;
+  E.separator_rule = L0.separator_rule;
+  E.rowptr.assign((size_t)n0 + 1, 0);
+  for (int64_t p = 0; p < n0; ++p) E.rowptr[p + 1] = E.rowptr[p] + (L0.rowptr[p + 1] - L0.rowptr[p]) + extra[p + 1];
+  const int64_t total = E.rowptr[n0];
+  E.colpos.resize((size_t)total);
+  E.vals.resize((size_t)total);
+  E.src.resize((size_t)total);
+  std::vector<int64_t> fill((size_t)n0);
+#pragma omp parallel for schedule(dynamic, 256)
+  for (int64_t p = 0; p < n0; ++p) {
+    int64_t w = E.rowptr[p];
+    for (int64_t e = L0.rowptr[p]; e < L0.rowptr[p + 1]; ++e, ++w) {
+      E.colpos[w] = L0.colpos[e]; E.vals[w] = L0.vals[e]; E.src[w] = L0.src[e];
+    }
+    fill[p] = w;
+  }
+  for (size_t li = 1; li < levels.size(); ++li) {
+    const HostLevel& L = levels[li];
+    // a vertex is a row of a level at most once, so no two rows of L write the same target row
+#pragma omp parallel for schedule(dynamic, 256)
+    for (int64_t p = 0; p < L.n_i; ++p) {
+      const int64_t tp = pos0[L.perm[p]];
+      int64_t w = fill[tp];
+      for (int64_t e = L.rowptr[p]; e < L.rowptr[p + 1]; ++e, ++w) {
+        E.colpos[w] = pos0[L.perm[L.colpos[e]]]; E.vals[w] = L.vals[e]; E.src[w] = L.src[e];
+      }
+      fill[tp] = w;
+    }
+    HostLevel& S = exec[li];
+    S.n_i = L.n_i;
+    S.perm = L.perm;
+    S.rowptr.assign((size_t)L.n_i + 1, 0);
+    S.separator_rule = L.separator_rule;
+  }
+  // rows that received entries: order by column position again (keys are distinct inside a row)
+#pragma omp parallel
+  {
+    std::vector<uint64_t> key;
+    std::vector<float> tv;
+    std::vector<uint32_t> ts;
+#pragma omp for schedule(dynamic, 256)
+    for (int64_t p = 0; p < n0; ++p) {
+      if (extra[p + 1] == 0) continue;
+      const int64_t w0 = E.rowptr[p], len = E.rowptr[p + 1] - w0;
+      key.resize((size_t)len); tv.resize((size_t)len); ts.resize((size_t)len);
+      for (int64_t q = 0; q < len; ++q) key[q] = ((uint64_t)(uint32_t)E.colpos[w0 + q] << 32) | (uint64_t)q;
+      std::sort(key.begin(), key.end());
+      for (int64_t q = 0; q < len; ++q) {
+        const int64_t from = w0 + (int64_t)(key[q] & 0xffffffffu);
+        tv[q] = E.vals[from]; ts[q] = E.src[from];
+      }
+      for (int64_t q = 0; q < len; ++q) {
+        E.colpos[w0 + q] = (int32_t)(key[q] >> 32); E.vals[w0 + q] = tv[q]; E.src[w0 + q] = ts[q];
+      }
+    }
+  }
+}
 
-int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const PackOptions& opt,
-               Image& img, std::string& err) {
+int pack_levels(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const PackOptions& opt,
+                Image& img, std::string& err) {
   img.levels.clear();
   img.max_partials = 0;
   img.max_stage_rows = 0;
   img.max_window_span = 0;
   img.max_panel_slots = 0;
+  img.max_corner_items = 0;
   const int64_t short_max = opt.short_max < 0 ? 0 : opt.short_max;
   const int64_t chunk_nnz = opt.chunk_nnz < 1 ? 1 : opt.chunk_nnz;
   const int64_t chunk_min = opt.chunk_min < 1 ? 1 : (opt.chunk_min > chunk_nnz ? chunk_nnz : opt.chunk_min);
@@ -183,11 +291,14 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
           for (; p1 < blk1 && p1 - p0 < rows_cap; ++p1) {
             const int32_t* cb = L.colpos.data() + L.rowptr[p1];
             const int32_t* ce = L.colpos.data() + L.rowptr[p1 + 1];
-            const int32_t* cd = std::lower_bound(cb, ce, (int32_t)b);     // first diagonal-block entry
-            if (cd == ce) continue;                                       // first-block-column entries only
-            const int64_t nmin = std::min<int64_t>(cmin, *cd), nmax = std::max<int64_t>(cmax, *(ce - 1));
+            // the row's diagonal-block entries (with fused levels a row also holds entries of
+            // other blocks; those are read from memory like the first-block-column entries)
+            const int32_t* cd = std::lower_bound(cb, ce, (int32_t)blk0);
+            const int32_t* cx = std::lower_bound(cd, ce, (int32_t)blk1);
+            if (cd == cx) continue;                                       // no diagonal-block entry
+            const int64_t nmin = std::min<int64_t>(cmin, *cd), nmax = std::max<int64_t>(cmax, *(cx - 1));
             if (nmax - nmin + 1 > span_cap) break;
-            cmin = nmin; cmax = nmax; dnnz += ce - cd;
+            cmin = nmin; cmax = nmax; dnnz += cx - cd;
           }
           if (p1 == p0) { ++p0; continue; }                               // one row alone exceeds the span
           if (cmax >= 0 && (double)dnnz >= opt.window_reuse * (double)(cmax - cmin + 1)) {
@@ -323,6 +434,65 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
         for (int64_t bi = 0; bi < n_bins; ++bi) P.panel_ptr[bi + 1] = bin_len[bi];
         P.nnz_panel = nnz_p;
         P.n_panel_rows = n_cand;
+      }
+    }
+
+    // ---- dense corner ----------------------------------------------------------------------------
+    if (opt.corner && im.staged && classes == 0 && P.panel_pos.empty() && opt.corner_min_tile > 0) {
+      const int64_t max_s = std::min<int64_t>(head, std::max<int64_t>(0, opt.corner_max)) / kCornerTile;   // tiles per side considered
+      if (max_s >= 1) {
+        std::vector<uint32_t> cnt((size_t)(max_s * max_s), 0);
+        const int64_t lim = max_s * kCornerTile;
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int64_t ip = 0; ip < max_s; ++ip)
+          for (int64_t p = ip * kCornerTile; p < (ip + 1) * kCornerTile; ++p) {
+            const int32_t* cb = L.colpos.data() + L.rowptr[p];
+            const int32_t* ce = std::lower_bound(cb, L.colpos.data() + L.rowptr[p + 1], (int32_t)lim);
+            for (const int32_t* c = cb; c < ce; ++c) ++cnt[(size_t)(ip * max_s + *c / kCornerTile)];
+          }
+        // the largest corner whose outermost band of tiles is still dense enough
+        int64_t side = 0;
+        for (int64_t sd = max_s; sd >= 1; --sd) {
+          int64_t band = 0;
+          for (int64_t t = 0; t < sd; ++t) band += cnt[(size_t)((sd - 1) * max_s + t)] + (t < sd - 1 ? cnt[(size_t)(t * max_s + sd - 1)] : 0);
+          if (band >= (int64_t)opt.corner_min_tile * (2 * sd - 1)) { side = sd; break; }
+        }
+        int64_t nnz_c = 0;
+        for (int64_t i = 0; i < side; ++i) for (int64_t j = 0; j < side; ++j) nnz_c += cnt[(size_t)(i * max_s + j)];
+        // worth its launches only when it holds a fair share of the level
+        if (side >= 1 && (double)nnz_c >= 0.02 * (double)lev_nnz) {
+          P.corner = side * kCornerTile;
+          P.nnz_corner = nnz_c;
+          P.skip.assign(L.n_i, 0);
+#pragma omp parallel for schedule(dynamic, 256)
+          for (int64_t p = 0; p < P.corner; ++p) {
+            const int32_t* cb = L.colpos.data() + L.rowptr[p];
+            P.skip[p] = (uint32_t)(std::lower_bound(cb, L.colpos.data() + L.rowptr[p + 1], (int32_t)P.corner) - cb);
+          }
+          // work items: runs of tiles of one row panel holding about the same number of entries;
+          // enough of them to spread over all compute units, few enough to keep the partial
+          // results (256 rows per item) small
+          const int64_t target = std::max<int64_t>(8192, nnz_c / 2048);
+          P.corner_panel.push_back(0);
+          for (int64_t i = 0; i < side; ++i) {
+            int64_t in_item = 0;
+            bool open = false;
+            for (int64_t j = 0; j < side; ++j) {
+              const uint32_t c = cnt[(size_t)(i * max_s + j)];
+              if (c == 0) continue;
+              if (!open || in_item >= target) {
+                P.corner_items.push_back((uint32_t)P.corner_cnt.size());
+                open = true;
+                in_item = 0;
+              }
+              P.corner_cnt.push_back(c);
+              P.corner_ij.push_back((uint32_t)((i << 16) | j));
+              in_item += c;
+            }
+            P.corner_panel.push_back((uint32_t)P.corner_items.size());
+          }
+          P.corner_items.push_back((uint32_t)P.corner_cnt.size());
+        }
       }
     }
 
@@ -497,7 +667,7 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
       ptr.push_back((uint32_t)at);
       list_nnz[list] = at - at0;
     }
-    if (at + nnz_w + P.nnz_panel != lev_nnz) { err = "work lists do not cover the level"; return ARROW_EINTERNAL; }
+    if (at + nnz_w + P.nnz_panel + P.nnz_corner != lev_nnz) { err = "work lists do not cover the level"; return ARROW_EINTERNAL; }
     P.wrow_ptr.reserve(P.wrow_pos.size() + 1);
     for (int32_t p : P.wrow_pos) { P.wrow_ptr.push_back((uint32_t)at); at += L.rowptr[p + 1] - L.rowptr[p]; }
     P.wrow_ptr.push_back((uint32_t)at);
@@ -510,6 +680,8 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
       }
       P.panel_ptr[n_bins] = (uint32_t)at;
     }
+    P.corner_first.reserve(P.corner_cnt.size());
+    for (uint32_t c : P.corner_cnt) { P.corner_first.push_back((uint32_t)at); at += c; }
 
     // ---- staged head: buffer rows in class-major order ------------------------------------------
     if (im.staged) {
@@ -545,6 +717,11 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
     im.n_panel_bins = im.n_panel_groups * kDies * kPanelBins;
     if (im.n_panel_groups * kPanelRows > img.max_panel_slots) img.max_panel_slots = im.n_panel_groups * kPanelRows;
     im.nnz_panel = P.nnz_panel;
+    im.corner = P.corner;
+    im.nnz_corner = P.nnz_corner;
+    im.n_corner_tiles = (int64_t)P.corner_cnt.size();
+    im.n_corner_items = P.corner_items.empty() ? 0 : (int64_t)P.corner_items.size() - 1;
+    if (im.n_corner_items > img.max_corner_items) img.max_corner_items = im.n_corner_items;
     if (slots > img.max_partials) img.max_partials = slots;
 
     im.off_perm = total;        total = align_up(total + sizeof(int32_t) * (size_t)L.n_i);
@@ -566,6 +743,10 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
     im.off_wrow_win = total;    total = align_up(total + sizeof(uint32_t) * (size_t)im.n_wrows);
     im.off_panel_ptr = total;   total = align_up(total + sizeof(uint32_t) * (size_t)(im.n_panel_bins + 1));
     im.off_panel_y = total;     total = align_up(total + sizeof(int32_t) * (size_t)im.n_panel_groups * kPanelRows);
+    im.off_corner_tiles = total; total = align_up(total + sizeof(uint32_t) * (size_t)im.n_corner_tiles * kCornerTileWords);
+    im.off_corner_items = total; total = align_up(total + sizeof(uint32_t) * (size_t)(im.n_corner_items + 1));
+    im.off_corner_panel = total; total = align_up(total + sizeof(uint32_t) * (size_t)(im.corner / kCornerTile + 1));
+    im.off_corner_y = total;     total = align_up(total + sizeof(int32_t) * (size_t)im.corner);
     im.off_entries = total;     total = align_up(total + sizeof(Entry) * (size_t)lev_nnz);
     im.map_offset = map_total;  map_total += lev_nnz;
     img.levels.push_back(im);
@@ -711,17 +892,23 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
           const int32_t p = P.wrow_pos[wr];
           wy[wr] = L.perm[p];
           wwin[wr] = T.win_begin;
-          int64_t src = L.rowptr[p];
+          // entries outside the tile's window (first block column; other blocks when levels are
+          // fused) first, then the window entries
+          const int64_t w_lo = T.win_begin, w_hi = (int64_t)T.win_begin + T.win_count;
           uint32_t e = P.wrow_ptr[wr];
-          uint32_t mid = e;
-          for (; src < L.rowptr[p + 1]; ++src, ++e) {
+          for (int64_t src = L.rowptr[p]; src < L.rowptr[p + 1]; ++src) {
             const int32_t q = L.colpos[src];
-            if (q < b) { ent[e].xrow = L.perm[q]; mid = e + 1; }
-            else ent[e].xrow = q - (int32_t)T.win_begin;
-            ent[e].val = L.vals[src];
-            emap[e] = L.src[src];
+            if (q >= w_lo && q < w_hi) continue;
+            ent[e].xrow = L.perm[q]; ent[e].val = L.vals[src]; emap[e] = L.src[src];
+            ++e;
           }
-          wmid[wr] = mid;
+          wmid[wr] = e;
+          for (int64_t src = L.rowptr[p]; src < L.rowptr[p + 1]; ++src) {
+            const int32_t q = L.colpos[src];
+            if (q < w_lo || q >= w_hi) continue;
+            ent[e].xrow = q - (int32_t)T.win_begin; ent[e].val = L.vals[src]; emap[e] = L.src[src];
+            ++e;
+          }
         }
       }
     }
@@ -765,6 +952,63 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
         }
       }
     }
+    // dense corner: per row panel the rows' leading entries (columns inside the corner) are dealt
+    // to the panel's tiles; inside a tile they stay ordered by row, then column, and are cut into
+    // kCornerRuns runs at row boundaries, as equal as the rows allow
+    if (im.n_corner_tiles) {
+      uint32_t* tw = reinterpret_cast<uint32_t*>(base + im.off_corner_tiles);
+      std::memcpy(base + im.off_corner_items, P.corner_items.data(), sizeof(uint32_t) * P.corner_items.size());
+      std::memcpy(base + im.off_corner_panel, P.corner_panel.data(), sizeof(uint32_t) * P.corner_panel.size());
+      int32_t* cy = reinterpret_cast<int32_t*>(base + im.off_corner_y);
+      for (int64_t p = 0; p < im.corner; ++p) cy[p] = L.perm[p];
+      const int64_t side = im.corner / kCornerTile;
+      // first listed tile of every panel (tiles are listed panel by panel, column tiles ascending)
+      std::vector<int64_t> panel_tile((size_t)side + 1, 0);
+      for (uint32_t ij : P.corner_ij) ++panel_tile[(size_t)(ij >> 16) + 1];
+      for (int64_t i = 0; i < side; ++i) panel_tile[i + 1] += panel_tile[i];
+#pragma omp parallel
+      {
+        std::vector<int64_t> tile_of((size_t)side);       // column tile -> listed tile of this panel, -1 = empty
+        std::vector<uint32_t> fill;
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t ip = 0; ip < side; ++ip) {
+          std::fill(tile_of.begin(), tile_of.end(), -1);
+          for (int64_t t = panel_tile[ip]; t < panel_tile[ip + 1]; ++t) tile_of[P.corner_ij[t] & 0xffffu] = t;
+          fill.assign((size_t)(panel_tile[ip + 1] - panel_tile[ip]), 0);
+          for (int64_t r = 0; r < kCornerTile; ++r) {
+            const int64_t p = ip * kCornerTile + r;
+            int64_t src = L.rowptr[p];
+            for (uint32_t e = 0; e < P.skip[p]; ++e, ++src) {
+              const int32_t q = L.colpos[src];
+              const int64_t t = tile_of[q / kCornerTile];
+              const uint32_t at_e = P.corner_first[t] + fill[(size_t)(t - panel_tile[ip])]++;
+              ent[at_e].xrow = (int32_t)(((uint32_t)r << 16) | (uint32_t)(q % kCornerTile));
+              ent[at_e].val = L.vals[src];
+              emap[at_e] = L.src[src];
+            }
+          }
+          for (int64_t t = panel_tile[ip]; t < panel_tile[ip + 1]; ++t) {
+            uint32_t* w = tw + (size_t)t * kCornerTileWords;
+            const uint32_t first = P.corner_first[t], cnt_t = P.corner_cnt[t];
+            // run r starts at the first row boundary at or after r * cnt / kCornerRuns
+            uint32_t pos = 0;
+            w[0] = first;
+            for (int r = 1; r < kCornerRuns; ++r) {
+              const uint32_t want = (uint32_t)((uint64_t)cnt_t * (uint64_t)r / kCornerRuns);
+              if (pos < want) {
+                pos = want;
+                while (pos < cnt_t && pos > 0 &&
+                       ((uint32_t)ent[first + pos].xrow >> 16) == ((uint32_t)ent[first + pos - 1].xrow >> 16)) ++pos;
+              }
+              w[r] = first + pos;
+            }
+            w[kCornerRuns] = first + cnt_t;
+            w[kCornerRuns + 1] = (P.corner_ij[t] & 0xffffu) * kCornerTile;   // first staged head row of the tile
+            w[kCornerRuns + 2] = P.corner_ij[t] >> 16;                       // row panel
+          }
+        }
+      }
+    }
     // distinct X rows per list (what each kernel must read at least once)
     std::vector<uint8_t> seen((size_t)n, 0);
     for (int list = 0; list < 2; ++list) {
@@ -790,8 +1034,8 @@ int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const
 // ordered, row ids inside X / the staging buffer / the LDS window, every partial slot written
 // by exactly one item and owned by exactly one split row, and every row of a level produced
 // exactly once (level 0: every vertex).
-int verify_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const Image& img,
-                 std::string& err) {
+int verify_levels(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const Image& img,
+                  std::string& err) {
   if (img.levels.size() != levels.size()) { err = "level count differs"; return ARROW_EINTERNAL; }
   const unsigned char* base = img.bytes.data();
   // the entry map is a bijection between the image's entries and the caller's nonzeros
@@ -948,6 +1192,59 @@ int verify_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, con
         }
       }
     }
+    // dense corner: items and panels partition the tiles; a tile's runs cover its entries in
+    // order, never share a row, and every entry names a row of the tile's panel and a staged head
+    // row of the tile's column range
+    if (im.n_corner_tiles || im.corner) {
+      const uint32_t* tw = reinterpret_cast<const uint32_t*>(base + im.off_corner_tiles);
+      const uint32_t* items = reinterpret_cast<const uint32_t*>(base + im.off_corner_items);
+      const uint32_t* pptr = reinterpret_cast<const uint32_t*>(base + im.off_corner_panel);
+      const int32_t* cy = reinterpret_cast<const int32_t*>(base + im.off_corner_y);
+      const int64_t side = im.corner / kCornerTile;
+      if (im.corner % kCornerTile || im.corner > im.n_stage || !im.staged || im.classes != 0 || side < 1 ||
+          im.n_corner_items < 1 || im.n_corner_items > img.max_corner_items) { err = "bad corner geometry"; return ARROW_EINTERNAL; }
+      for (int64_t p = 0; p < im.corner; ++p)
+        if (cy[p] != L.perm[p]) { err = "corner row table differs from the permutation"; return ARROW_EINTERNAL; }
+      if (items[0] != 0 || (int64_t)items[im.n_corner_items] != im.n_corner_tiles || pptr[0] != 0 ||
+          (int64_t)pptr[side] != im.n_corner_items) { err = "corner items do not cover the tiles"; return ARROW_EINTERNAL; }
+      for (int64_t ip = 0; ip < side; ++ip) {
+        if (pptr[ip] > pptr[ip + 1]) { err = "corner panel table not monotone"; return ARROW_EINTERNAL; }
+        for (uint32_t it = pptr[ip]; it < pptr[ip + 1]; ++it) {
+          if (items[it] >= items[it + 1]) { err = "empty corner item"; return ARROW_EINTERNAL; }
+          for (uint32_t t = items[it]; t < items[it + 1]; ++t) {
+            const uint32_t* w = tw + (size_t)t * kCornerTileWords;
+            const uint32_t col0 = w[kCornerRuns + 1];
+            if (w[kCornerRuns + 2] != (uint32_t)ip || col0 % kCornerTile || (int64_t)col0 + kCornerTile > im.corner ||
+                (t > items[pptr[ip]] && col0 <= tw[(size_t)(t - 1) * kCornerTileWords + kCornerRuns + 1])) {
+              err = "corner tile in the wrong panel or out of order"; return ARROW_EINTERNAL;
+            }
+            if (w[0] != expect) { err = "corner tile offsets out of order"; return ARROW_EINTERNAL; }
+            int64_t last_row = -1;
+            for (int r = 0; r < kCornerRuns; ++r) {
+              const uint32_t lo = w[r], hi = w[r + 1];
+              if (hi < lo || (int64_t)hi > lev_nnz) { err = "corner run offsets out of order"; return ARROW_EINTERNAL; }
+              for (uint32_t e = lo; e < hi; ++e) {
+                const uint32_t code = (uint32_t)ent[e].xrow;
+                const int64_t row = code >> 16, col = code & 0xffffu;
+                if (row >= kCornerTile || col >= kCornerTile) { err = "corner entry outside its tile"; return ARROW_EINTERNAL; }
+                if (e == lo ? row <= last_row
+                            : (row < last_row || (row == last_row && col <= (int64_t)((uint32_t)ent[e - 1].xrow & 0xffffu)))) {
+                  err = "corner runs share a row or are not ordered"; return ARROW_EINTERNAL;
+                }
+                last_row = row;
+                const int32_t y = cy[ip * kCornerTile + row];
+                const int64_t xr = stage_perm[col0 + col];
+                if (xr < 0 || xr >= n) { err = "X row out of range"; return ARROW_EINTERNAL; }
+                checksum[y] += (double)ent[e].val * (double)(1 + xr);
+                ent_row[e] = y;
+              }
+              covered += hi - lo;
+            }
+            expect = w[kCornerRuns];
+          }
+        }
+      }
+    }
     {
       // the map sends every image entry to a nonzero of this level with the same value and row
       std::vector<uint32_t> order((size_t)lev_nnz);
@@ -983,6 +1280,71 @@ int verify_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, con
     (void)b;
   }
   return ARROW_OK;
+}
+
+}  // namespace
+
+int pack_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const PackOptions& opt,
+               Image& img, std::string& err) {
+  img.fused = false;
+  if (opt.fuse_levels && levels.size() > 1 && levels[0].n_i == n) {
+    std::vector<HostLevel> exec;
+    std::vector<int64_t> fused_from;
+    int64_t total = 0;
+    for (const HostLevel& L : levels) total += L.rowptr[L.n_i];
+    if (total < 0xffffffffLL - 4096) {
+      fuse_levels(levels, exec, fused_from);
+      const int rc = pack_levels(n, b, exec, opt, img, err);
+      if (rc != ARROW_OK) return rc;
+      img.fused = true;
+      for (size_t li = 1; li < levels.size(); ++li) img.levels[0].nnz_fused += fused_from[li];
+      return ARROW_OK;
+    }
+  }
+  return pack_levels(n, b, levels, opt, img, err);
+}
+
+int verify_image(int64_t n, int32_t b, const std::vector<HostLevel>& levels, const Image& img,
+                 std::string& err) {
+  if (!img.fused) return verify_levels(n, b, levels, img, err);
+  // fused levels: the execution form must hold, vertex by vertex, exactly the entries of all
+  // levels (same count, same nonzeros of the caller's arrays, same value bits, same column
+  // vertex), and the image must match the execution form
+  std::vector<HostLevel> exec;
+  std::vector<int64_t> fused_from;
+  fuse_levels(levels, exec, fused_from);
+  const HostLevel& E = exec[0];
+  if (E.n_i != n) { err = "fused level 0 does not cover every vertex"; return ARROW_EINTERNAL; }
+  int64_t total = 0;
+  for (const HostLevel& L : levels) total += L.rowptr[L.n_i];
+  if (E.rowptr[E.n_i] != total) { err = "fused level holds another number of entries"; return ARROW_EINTERNAL; }
+  // nonzero of the caller's arrays -> (row vertex, column vertex, value bits), from the levels
+  std::vector<int32_t> src_row((size_t)total, -1), src_col((size_t)total, -1);
+  std::vector<uint32_t> src_bits((size_t)total, 0);
+  for (const HostLevel& L : levels)
+    for (int64_t p = 0; p < L.n_i; ++p)
+      for (int64_t e = L.rowptr[p]; e < L.rowptr[p + 1]; ++e) {
+        const uint32_t s = L.src[e];
+        if ((int64_t)s >= total || src_row[s] != -1) { err = "levels: source indices are not a bijection"; return ARROW_EINTERNAL; }
+        src_row[s] = L.perm[p]; src_col[s] = L.perm[L.colpos[e]];
+        std::memcpy(&src_bits[s], &L.vals[e], sizeof(uint32_t));
+      }
+  std::vector<uint8_t> hit((size_t)total, 0);
+  for (int64_t p = 0; p < E.n_i; ++p)
+    for (int64_t e = E.rowptr[p]; e < E.rowptr[p + 1]; ++e) {
+      const uint32_t s = E.src[e];
+      uint32_t bits;
+      std::memcpy(&bits, &E.vals[e], sizeof(uint32_t));
+      if ((int64_t)s >= total || hit[s] || src_row[s] != E.perm[p] || src_col[s] != E.perm[E.colpos[e]] ||
+          src_bits[s] != bits || (e > E.rowptr[p] && E.colpos[e - 1] >= E.colpos[e])) {
+        err = "fused level: an entry differs from the level it came from"; return ARROW_EINTERNAL;
+      }
+      hit[s] = 1;
+    }
+  if (img.levels.size() != levels.size() || img.levels[0].nnz_fused != total - levels[0].rowptr[levels[0].n_i]) {
+    err = "fused entry count differs"; return ARROW_EINTERNAL;
+  }
+  return verify_levels(n, b, exec, img, err);
 }
 
 }  // namespace arrow

@@ -358,6 +358,11 @@ def test_error_paths():
     dict(ARROW_WINDOW_ROWS="64", ARROW_HEAD_BY_ID="0"),
     dict(ARROW_STAGE_SHORT="1"), dict(ARROW_STAGE_SHORT="0", ARROW_EMPTY_LAST="0"),
     dict(ARROW_STAGE_SHORT="1", ARROW_EMPTY_LAST="1", ARROW_SHORT_MAX="64", ARROW_CLASSES="8", ARROW_CLASS_MIN="2"),
+    dict(ARROW_CORNER="1"), dict(ARROW_CORNER="1", ARROW_HUBS_FIRST="65536", ARROW_CORNER_MIN_TILE="1"),
+    dict(ARROW_CORNER="1", ARROW_HUBS_FIRST="300", ARROW_CORNER_MAX="256", ARROW_FUSE_LEVELS="0"),
+    dict(ARROW_CORNER="1", ARROW_HUBS_FIRST="65536", ARROW_CORNER_MIN_TILE="4000", ARROW_SHORT_MAX="0"),
+    dict(ARROW_FUSE_LEVELS="0"), dict(ARROW_FUSE_LEVELS="0", ARROW_WINDOW_ROWS="64", ARROW_CHUNK_NNZ="40"),
+    dict(ARROW_FUSE_LEVELS="0", ARROW_PANEL="1", ARROW_WINDOW_ROWS="32", ARROW_PANEL_MIN="1"),
 ])
 def test_packed_image_self_check_under_pack_options(monkeypatch, env):
     for name, v in env.items():
@@ -373,18 +378,29 @@ def test_packed_image_self_check_under_pack_options(monkeypatch, env):
 
 @pytest.mark.parametrize("env", [dict(), dict(ARROW_PANEL="1", ARROW_WINDOW_ROWS="64"),
                                  dict(ARROW_CLASSES="8", ARROW_CLASS_MIN="2", ARROW_CLASS_GRAN="16")])
-def test_entry_map_is_a_bijection_onto_the_nonzeros(monkeypatch, env):
+@pytest.mark.parametrize("fuse", ["0", "1"])
+def test_entry_map_is_a_bijection_onto_the_nonzeros(monkeypatch, env, fuse):
+    monkeypatch.setenv("ARROW_FUSE_LEVELS", fuse)
     for name, v in env.items():
         monkeypatch.setenv(name, v)
     w = synth.make_config(0)
     h = binding.arrow_decompose(w.rowptr, w.colidx, w.vals, w.b)
     try:
+        binding.arrow_self_check(h)
         emap = binding.arrow_export_entry_map(h)
         assert emap.shape == (w.nnz,) and np.array_equal(np.sort(emap), np.arange(w.nnz, dtype=np.uint32))
+        n_levels = binding.arrow_info(h)["levels"]
+        assert n_levels >= 2
+        fused = binding.arrow_level_info(h, 0)["nnz_fused"]
+        if fuse == "1":
+            # one image level holds every entry: the later levels' entries sit with the level-0 rows
+            assert fused == sum(binding.arrow_level_info(h, i)["nnz"] for i in range(1, n_levels))
+            return
+        assert fused == 0
         # level by level the map's image is that level's set of nonzeros (as (row, column, value))
         at = 0
         csr_row = np.repeat(np.arange(w.n), np.diff(w.rowptr))
-        for i in range(binding.arrow_info(h)["levels"]):
+        for i in range(n_levels):
             perm, r, c, v = binding.arrow_export_level(h, i)
             src = np.sort(emap[at:at + len(v)])
             at += len(v)
@@ -398,16 +414,100 @@ def test_entry_map_is_a_bijection_onto_the_nonzeros(monkeypatch, env):
         binding.arrow_destroy(h)
 
 
+def _banded_with_far_entries(n=6000, seed=12):
+    rng = np.random.default_rng(seed)
+    rows, cols = [], []
+    for d in (-3, -2, -1, 0, 1, 2, 3):
+        i = np.arange(max(0, -d), min(n, n - d))
+        rows.append(i); cols.append(i + d)
+    far = rng.integers(0, n, (3000, 2))
+    rows += [far[:, 0], far[:, 1]]; cols += [far[:, 1], far[:, 0]]
+    rows = np.concatenate(rows); cols = np.concatenate(cols)
+    key = np.unique(rows.astype(np.int64) * n + cols)
+    return csr_from_coo(n, key // n, key % n, rng.uniform(-1, 1, len(key)))
+
+
+@pytest.mark.parametrize("fuse", ["0", "1"])
+def test_fused_levels_keep_the_decomposition_and_cover_every_entry(monkeypatch, fuse):
+    """The levels a handle exports do not depend on how the image executes them; with fused levels
+    the level-0 work lists hold every entry and the later levels hold none.  The operand (a band
+    cut at block boundaries plus far entries, separator rule off) has several levels, and LDS-window
+    tiles whose rows also carry entries of other blocks once the levels are fused."""
+    monkeypatch.setenv("ARROW_SEPARATORS", "0")
+    monkeypatch.setenv("ARROW_WINDOW_REUSE_X10", "5")
+    monkeypatch.setenv("ARROW_WINDOW_SHARE_X1000", "0")
+    monkeypatch.setenv("ARROW_FUSE_LEVELS", fuse)
+    rp, ci, va = _banded_with_far_entries()
+    n, b = len(rp) - 1, 500
+    X = np.random.default_rng(5).standard_normal((n, 3)).astype(np.float32)
+    info, linfo, levels = full_check(rp, ci, va, b, X)          # runs arrow_self_check as well
+    assert info["levels"] >= 2
+    total = sum(li["nnz"] for li in linfo)
+    in_lists = [li["nnz_rows"] + li["nnz_chunks"] + li["nnz_window"] + li["nnz_panel"] + li["nnz_corner"] for li in linfo]
+    if fuse == "1":
+        assert in_lists[0] == total and all(x == 0 for x in in_lists[1:])
+        assert linfo[0]["nnz_fused"] == total - linfo[0]["nnz"]
+    else:
+        assert in_lists == [li["nnz"] for li in linfo] and linfo[0]["nnz_fused"] == 0
+    assert sum(li["window_tiles"] for li in linfo) > 0
+    # the exported decomposition is the same either way
+    monkeypatch.setenv("ARROW_FUSE_LEVELS", "1" if fuse == "0" else "0")
+    _, _, other = decompose_and_export(rp, ci, va, b)
+    assert len(other) == len(levels)
+    for a, c in zip(levels, other):
+        for x, y in zip(a, c):
+            assert np.array_equal(x.view(np.uint32) if x.dtype == np.float32 else x,
+                                  y.view(np.uint32) if y.dtype == np.float32 else y)
+
+
+def test_dense_corner_takes_the_leading_entries_of_its_rows(monkeypatch):
+    """With the hubs leading the head, rows and columns [0, S) of level 0 form the dense corner:
+    S is a multiple of 256, the corner holds exactly the entries (p, q) with p, q < S, and the
+    work lists hold the rest."""
+    monkeypatch.setenv("ARROW_CORNER", "1")
+    monkeypatch.setenv("ARROW_HUBS_FIRST", "65536")
+    w = synth.make_config(3, shrink=8)                   # R-MAT scale 15, b = 1024
+    h = binding.arrow_decompose(w.rowptr, w.colidx, w.vals, w.b)
+    try:
+        binding.arrow_self_check(h)
+        li = binding.arrow_level_info(h, 0)
+        S = li["corner"]
+        assert S > 0 and S % 256 == 0 and S <= w.b
+        perm, r, c, v = binding.arrow_export_level(h, 0)
+        inside = np.count_nonzero((r < S) & (c < S))
+        assert li["nnz_corner"] == inside and inside >= 0.02 * li["nnz"]
+        assert 1 <= li["corner_items"] <= li["corner_tiles"] <= (S // 256) ** 2
+        assert li["nnz_rows"] + li["nnz_chunks"] + li["nnz_window"] + li["nnz_corner"] == li["nnz"] + li["nnz_fused"]
+        assert binding.arrow_level_info(h, 1)["corner"] == 0          # later levels stage no head
+        with_corner = binding.arrow_workspace_bytes(h, 32)
+    finally:
+        binding.arrow_destroy(h)
+    monkeypatch.setenv("ARROW_CORNER_MIN_TILE", "100000")             # no band of tiles is that dense
+    h = binding.arrow_decompose(w.rowptr, w.colidx, w.vals, w.b)
+    assert binding.arrow_level_info(h, 0)["corner"] == 0
+    assert binding.arrow_workspace_bytes(h, 32) < with_corner         # the items' result rows are gone
+    binding.arrow_destroy(h)
+
+
 def test_head_order_inside_the_head(monkeypatch):
     """The arrow shape only fixes WHICH vertices are in the head; inside it they sit in id order
     (so that position order follows the caller's column order), or by falling degree on request.
     Both give the same head set and the same level sizes."""
     w = synth.make_config(0)
+    deg = np.diff(w.rowptr) + np.bincount(w.colidx, minlength=w.n)
+    deg -= 2 * np.array([np.any(w.colidx[w.rowptr[v]:w.rowptr[v + 1]] == v) for v in range(w.n)])
+    monkeypatch.setenv("ARROW_HUBS_FIRST", "100")      # 100 hubs by falling degree, then id order
+    h = binding.arrow_decompose(w.rowptr, w.colidx, w.vals, w.b)
+    mixed = binding.arrow_export_level(h, 0)[0][:w.b]
+    binding.arrow_destroy(h)
+    assert np.all(np.diff(deg[mixed[:100]]) <= 0) and np.all(np.diff(mixed[100:]) > 0)
+    assert deg[mixed[:100]].min() >= deg[mixed[100:]].max()
+    monkeypatch.setenv("ARROW_HUBS_FIRST", "0")
     h = binding.arrow_decompose(w.rowptr, w.colidx, w.vals, w.b)
     head_id = binding.arrow_export_level(h, 0)[0][:w.b]
     nnz_id = [binding.arrow_level_info(h, i)["nnz"] for i in range(binding.arrow_info(h)["levels"])]
     binding.arrow_destroy(h)
-    assert np.all(np.diff(head_id) > 0)
+    assert np.all(np.diff(head_id) > 0) and np.array_equal(np.sort(mixed), head_id)
     monkeypatch.setenv("ARROW_HEAD_BY_ID", "0")
     h = binding.arrow_decompose(w.rowptr, w.colidx, w.vals, w.b)
     head_deg = binding.arrow_export_level(h, 0)[0][:w.b]
@@ -435,7 +535,7 @@ def test_head_panels_take_the_sparse_head_rows(monkeypatch):
             want = (hh >= 8) & (hh < cap)
         assert li["panel_rows"] == np.count_nonzero(want) and li["nnz_panel"] == hh[want].sum()
         assert li["panel_bins"] % 256 == 0 and li["panel_bins"] >= li["panel_rows"]   # 8 x 32 streams per 256 rows
-        assert li["nnz_rows"] + li["nnz_chunks"] + li["nnz_window"] + li["nnz_panel"] == li["nnz"]
+        assert li["nnz_rows"] + li["nnz_chunks"] + li["nnz_window"] + li["nnz_panel"] + li["nnz_corner"] == li["nnz"] + li["nnz_fused"]
         assert binding.arrow_level_info(h, 1)["panel_rows"] == 0        # later levels stage no head
     finally:
         binding.arrow_destroy(h)

@@ -233,9 +233,13 @@ def test_dense_diagonal_blocks_use_lds_window_by_default(torch):
     op.close()
 
 
-def test_lds_window_on_a_later_level_accumulates(torch, monkeypatch):
+@pytest.mark.parametrize("fuse", ["0", "1"])
+def test_lds_window_on_a_later_level_accumulates(torch, monkeypatch, fuse):
     """Banded operator plus scattered far entries and a few hubs: with the separator rule off the
-    band is cut at block boundaries, so later levels own banded diagonal blocks and must add."""
+    band is cut at block boundaries, so later levels own banded diagonal blocks and must add
+    (levels run one after the other), or their entries join the window rows of level 0 and are
+    read from memory there (fused levels)."""
+    monkeypatch.setenv("ARROW_FUSE_LEVELS", fuse)
     monkeypatch.setenv("ARROW_SEPARATORS", "0")
     monkeypatch.setenv("ARROW_WINDOW_REUSE_X10", "5")
     monkeypatch.setenv("ARROW_WINDOW_SHARE_X1000", "0")
@@ -329,6 +333,72 @@ def test_directed_operands(torch, lower):
     arrow_checks.check_decomposition(n, *csr, b, levels)
     Yref, B = oracle.spmm(*csr, X)
     assert_within(Y, Yref, B)
+    op.close()
+
+
+@pytest.mark.parametrize("idx,shrink,k", [(3, 8, 128), (4, 8, 32), (2, 6, 36), (0, 0, 7)])
+def test_fused_and_separate_levels(torch, monkeypatch, idx, shrink, k):
+    """One launch set that sums over all arrow matrices (fused levels, the default) against one
+    launch set per level with a read-modify-write of Y in between: both within the bound of the
+    oracle, on operands with several levels."""
+    w = synth.make_config(idx, shrink=shrink)
+    X = synth.normal_matrix(w.n, k, seed=300 + k)
+    Yref, B = oracle.spmm(*csr_of(w), X)
+    seen = {}
+    for fuse in ("1", "0"):
+        monkeypatch.setenv("ARROW_FUSE_LEVELS", fuse)
+        op, Xd, Y = run_product(torch, csr_of(w), w.b, X)
+        lv = op.levels()
+        assert len(lv) >= 2
+        seen[fuse] = [l["nnz_rows"] + l["nnz_chunks"] + l["nnz_window"] + l["nnz_panel"] + l["nnz_corner"] for l in lv]
+        assert_within(Y, Yref, B)
+        Z = torch.from_numpy(X).cuda()
+        op.spmm_iter(Z, 2)
+        X2, E2 = oracle.spmm_iter(*csr_of(w), X, 2)
+        assert_within(Z.cpu().numpy(), X2, E2, scale=2)
+        op.close()
+    assert all(x == 0 for x in seen["1"][1:]) and all(x > 0 for x in seen["0"][1:])
+    assert sum(seen["1"]) == sum(seen["0"]) == w.nnz
+
+
+@pytest.mark.parametrize("env", [
+    dict(ARROW_HUBS_FIRST="65536"),
+    dict(ARROW_HUBS_FIRST="65536", ARROW_CORNER_MIN_TILE="1"),
+    dict(ARROW_HUBS_FIRST="300", ARROW_CORNER_MAX="256", ARROW_FUSE_LEVELS="0"),
+    dict(ARROW_HUBS_FIRST="0", ARROW_CORNER_MIN_TILE="200"),
+])
+@pytest.mark.parametrize("k", [1, 3, 16, 36, 64, 128, 130, 260])
+def test_dense_corner_tiles(torch, monkeypatch, env, k):
+    """The dense corner of the head block in LDS tiles (staged head rows and accumulators in LDS),
+    on and off, against the oracle; bitwise repeatable."""
+    w = synth.make_config(3, shrink=8)              # R-MAT scale 15, b = 1024: corners of 256 .. 1024
+    X = synth.normal_matrix(w.n, k, seed=500 + k)
+    Yref, B = oracle.spmm(*csr_of(w), X)
+    for name, v in env.items():
+        monkeypatch.setenv(name, v)
+    for corner in ("1", "0"):
+        monkeypatch.setenv("ARROW_CORNER", corner)
+        op, Xd, Y = run_product(torch, csr_of(w), w.b, X)
+        lv = op.levels()
+        assert (lv[0]["nnz_corner"] > 0) == (corner == "1")
+        assert_within(Y, Yref, B)
+        Y2 = op.spmm(Xd).cpu().numpy()
+        assert np.array_equal(Y.view(np.uint32), Y2.view(np.uint32))
+        op.close()
+
+
+def test_dense_corner_larger_operand_and_chained(torch, monkeypatch):
+    monkeypatch.setenv("ARROW_CORNER", "1")
+    monkeypatch.setenv("ARROW_HUBS_FIRST", "65536")
+    w = synth.make_config(4, shrink=6)              # Chung-Lu, 262144 vertices, k = 32, b = 4096, A^5
+    X = w.make_x()
+    op = binding.ArrowSpMM(*csr_of(w), w.b)
+    lv = op.levels()
+    assert lv[0]["corner"] >= 1024 and lv[0]["corner_items"] > lv[0]["corner"] // 256   # panels cut into several items
+    Xd = torch.from_numpy(X).cuda()
+    op.spmm_iter(Xd, w.l)
+    Xl, El = oracle.spmm_iter(*csr_of(w), X, w.l)
+    assert_within(Xd.cpu().numpy(), Xl, El, scale=w.l)
     op.close()
 
 

@@ -158,7 +158,29 @@ def test_head_panels(torch, monkeypatch, env, k):
     op.close()
 
 
-@pytest.mark.parametrize("env", [dict(), dict(ARROW_PANEL="1", ARROW_WINDOW_ROWS="64")])
+@pytest.mark.parametrize("env", [
+    dict(ARROW_HUBS_FIRST="65536"),
+    dict(ARROW_HUBS_FIRST="100", ARROW_CORNER_MAX="256", ARROW_CORNER_MIN_TILE="1", ARROW_FUSE_LEVELS="0"),
+])
+@pytest.mark.parametrize("k", [1, 3, 16, 36, 128, 260, 1030])
+def test_dense_corner(torch, monkeypatch, env, k):
+    """Entries that the product runs in the LDS tiles of the dense corner: their row is found
+    through the corner row table, their V row is a staged head row of the tile's column range."""
+    monkeypatch.setenv("ARROW_CORNER", "1")
+    for name, v in env.items():
+        monkeypatch.setenv(name, v)
+    w = synth.make_config(0)
+    U = synth.normal_matrix(w.n, k, seed=91 + k)
+    V = synth.normal_matrix(w.n, k, seed=92 + k)
+    op, _, _, S = run_sampled(torch, csr_of(w), w.b, U, V)
+    assert op.levels()[0]["nnz_corner"] > 0
+    Sref, B = oracle.sddmm(*csr_of(w), U, V)
+    assert_within(S, Sref, B)
+    op.close()
+
+
+@pytest.mark.parametrize("env", [dict(), dict(ARROW_PANEL="1", ARROW_WINDOW_ROWS="64"),
+                                 dict(ARROW_CORNER="1", ARROW_HUBS_FIRST="65536")])
 def test_image_order_output(torch, monkeypatch, env):
     """Option "sddmm_image_order": contiguous stores; the exported entry map brings S back to CSR order."""
     for name, v in env.items():
