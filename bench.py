@@ -5,6 +5,12 @@ One "step" is one whole product Y = A.X = sum_i P_i^T B_i (P_i X) through
 ``arrow_spmm`` (all levels, all kernels) on the R-MAT scale-23, k = 128 workload
 with inputs already resident in HBM.  Prints ONE JSON line.
 
+Timing: W untimed warm-up steps, then K steps between two device synchronisations on the host
+clock (``ms_per_step``, the figure ``value`` is computed from); after that the same K steps once
+more, each bracketed by HIP events on the launch stream (``per_call_ms``: median, min, mean),
+a pass with the library's per-launch events (``launch_ms``), and the bare row-gather yardstick
+(``roofline.gather_yardstick``).
+
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--shrink S]
 
 ``--op sddmm`` times the sampled dense-dense product S = A .* (U V^T) over the same arrow
@@ -37,6 +43,7 @@ def algorithmic_bytes_sddmm(levels, n, k):
         per[("chunks", i)] = 16 * L["nnz_chunks"] + 12 * L["chunks"] + 4 + row * (L["x_rows_chunks"] + L["chunks"] - L["chunks_partials"] + L["split_rows"])
         per[("window", i)] = 16 * L["nnz_window"] + 16 * L["window_rows"] + row * 2 * L["window_rows"]
         per[("panel", i)] = 16 * L["nnz_panel"] + 4 * L["panel_bins"] + row * 2 * L["panel_rows"]
+        per[("corner", i)] = 16 * L["nnz_corner"] + 4 * 67 * L["corner_tiles"] + row * 2 * L["corner"]
         per[("reduce", i)] = 0
         per[("stage", i)] = 0
     path = 16 * sum(L["nnz"] for L in levels) + 2 * row * n
@@ -65,11 +72,78 @@ def algorithmic_bytes(levels, n, k):
         # panels: entries, every staged head row once, the eight class results written and read,
         # Y read and written
         per[("panel", i)] = 8 * L["nnz_panel"] + 4 * L["panel_bins"] + row * (18 * L["panel_rows"]) if L["panel_rows"] else 0
-    # whole product: X is read at least once and Y written once, whatever the kernel split
-    path = sum(8 * L["nnz"] + 12 * (L["short_rows"] + L["chunks"] + L["window_rows"]) for L in levels) + 2 * row * n
-    path += sum(row * 3 * (L["short_rows"] + L["chunks"] - L["partials"] + L["split_rows"] + L["window_rows"])
-                for L in levels[1:])
+        # dense corner: entries, tile words, each tile's 256 staged rows once per tile, the items'
+        # result rows written and read, Y read and written
+        per[("corner", i)] = (8 * L["nnz_corner"] + 4 * 67 * L["corner_tiles"] + row * 256 * L["corner_tiles"]
+                              + row * (2 * 256 * L["corner_items"] + 2 * L["corner"])) if L["corner"] else 0
+    # whole product, as the method defines it (independent of how the image executes the levels):
+    # 8 B per stored entry and 12 B per work item, X read once and Y written once, and for every
+    # later level its active rows gathered again and added to Y (read + write)
+    path = sum(8 * L["nnz"] for L in levels) + 2 * row * n
+    path += sum(12 * (L["short_rows"] + L["chunks"] + L["window_rows"]) for L in levels)
+    path += sum(row * 3 * L["n_i"] for L in levels[1:])
     return per, path
+
+
+def per_call_events(torch, fn, steps):
+    """`steps` calls of fn, each bracketed by a pair of events on the current stream (the stream the
+    library launches on); returns the per-call times in ms."""
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    for a, b in pairs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    return [a.elapsed_time(b) for a, b in pairs]
+
+
+def call_stats(ms):
+    ms = sorted(ms)
+    return {"median": round(ms[len(ms) // 2], 4), "min": round(ms[0], 4), "mean": round(sum(ms) / len(ms), 4),
+            "max": round(ms[-1], 4), "calls": len(ms)}
+
+
+def gather_yardstick(torch, binding, X, n, k, dev, gathers=1 << 26):
+    """Bare gathers of whole rows of X (`arrow_probe_gather`), in G rows/s: rows drawn from an LDS
+    window, from 2 MiB per accelerator die (L2 hits), from the first 128 MiB (the size of the staged
+    head at the headline) and from all of X.  None where X is too small for a region."""
+    if k < 4 or k > 256 or k & (k - 1):
+        return None
+    row = 4 * k
+    out_bytes = binding.arrow_probe_gather_out_bytes(gathers)
+    out = torch.empty(out_bytes // 4, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    cases = {"lds_64KiB": ((64 << 10) // row, True, True), "l2_hit_2MiB_per_die": ((2 << 20) // row, True, False),
+             "shared_128MiB": ((128 << 20) // row, False, False), "all_of_X": (n, False, False)}
+    res = {}
+    for name, (rows, per_die, lds) in cases.items():
+        if rows < 1 or rows * (8 if per_die else 1) > n:
+            res[name] = None
+            continue
+        def run():
+            binding.arrow_probe_gather(X.data_ptr(), n, k, rows, per_die, lds, gathers, out.data_ptr(), out_bytes, stream)
+        run()
+        ms = per_call_events(torch, run, 3)
+        res[name] = round(gathers / (min(ms) * 1e-3) / 1e9, 2)
+    res["unit"] = "G rows/s"
+    res["row_bytes"] = row
+    res["rows_gathered"] = gathers
+    return res
+
+
+def stored_traffic(path, launch_nnz, launch_items):
+    """Counter bytes of a launch from a stored rocprofv3 summary, or None when there is none or when
+    it was taken on another image (its entry / item counts differ from the live ones)."""
+    if not os.path.exists(path):
+        return None, None
+    with open(path) as f:
+        rec = json.load(f)
+    src = os.path.relpath(path, ROOT)
+    fp = rec.get("launch")
+    if not fp or fp.get("nnz") != launch_nnz or fp.get("items") != launch_items:
+        return None, src + " (stale: taken on another packed image; ignored)"
+    return rec.get("hbm_bytes_per_launch"), src
 
 
 def bench_mttkrp(args, torch, binding, synth, dev) -> int:
@@ -94,6 +168,7 @@ def bench_mttkrp(args, torch, binding, synth, dev) -> int:
         op.mttkrp(B, C, A)
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    per_call = call_stats(per_call_events(torch, lambda: op.mttkrp(B, C, A), args.steps))
     R, nnz = w.R, w.nnz
     # factorize-and-fuse operation count: 2 per entry and column for the fibre sums, 2 per fibre
     # and column for the products with B (the paper's "Pairwise Contraction" count)
@@ -129,7 +204,14 @@ def bench_mttkrp(args, torch, binding, synth, dev) -> int:
             traffic = json.load(f).get("hbm_bytes_per_launch")
     roofline = {"bound": "hbm", "kernel": "mttkrp_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                "avg_launch_ms": round(k_ms, 4), "launches_per_step": 1, "algorithmic_bytes_per_launch": int(alg)}
+                "avg_launch_ms": round(k_ms, 4), "launches_per_step": 1, "algorithmic_bytes_per_launch": int(alg),
+                "traffic_source": os.path.relpath(tpath, ROOT) if traffic else None,
+                # the HBM figure is the required one, but it is not what holds this kernel back: its
+                # counter traffic is about its algorithmic bytes, the factor rows live in L2, and the
+                # time goes into gathering them from there
+                "limiter": "L2-to-L1 gather of factor rows (HBM traffic ~ algorithmic bytes)",
+                "gathered_rows_per_launch": int(nnz + info["fibers"]), "row_bytes": row,
+                "gather_Grows_per_s": round((nnz + info["fibers"]) / (k_ms * 1e-3) / 1e9, 2) if k_ms > 0 else None}
     cpu_baseline = None
     check = None
     if not args.no_cpu_baseline:
@@ -161,11 +243,11 @@ def bench_mttkrp(args, torch, binding, synth, dev) -> int:
     out = {
         "metric": "fp32 order-3 MTTKRP GFLOP/s (2*nnz*R + 2*fibres*R), factorize-and-fuse over compressed sparse fibres",
         "value": round(gflops, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": None, "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "dims": list(w.dims), "nnz": nnz, "R": R, "fibers": info["fibers"],
                    "items": info["items"], "op": "mttkrp"},
-        "roofline": roofline, "cpu_baseline": cpu_baseline,
+        "per_call_ms": per_call, "roofline": roofline, "cpu_baseline": cpu_baseline,
         "launch_ms": {"mttkrp_kernel": round(k_ms, 4), "reduce_kernel": round(r_ms, 4)},
         "host_seconds": {"generate": round(t_gen, 1), "build_upload": round(t_build, 1)},
         "check": check,
@@ -189,6 +271,7 @@ def main() -> int:
                     help="also run this many plain device copies Y <- X (known HBM traffic: n*k*4 read + "
                          "n*k*4 written each) so that counter runs can be scaled")
     ap.add_argument("--no-profile-pass", action="store_true", help="skip the per-kernel event pass")
+    ap.add_argument("--no-gather-yardstick", action="store_true", help="skip the bare row-gather probes")
     ap.add_argument("--kc", type=int, default=None)
     ap.add_argument("--op", choices=("spmm", "sddmm", "mttkrp"), default="spmm",
                     help="spmm: Y = A.X (the headline); sddmm: S = A .* (U V^T) on the same layout; "
@@ -254,6 +337,8 @@ def main() -> int:
     ms_per_step = elapsed * 1e3 / args.steps
     flops = 2.0 * nnz * k * l
     gflops = flops / (ms_per_step * 1e-3) / 1e9
+    # the same K steps again, each bracketed by events on the launch stream
+    per_call = call_stats(per_call_events(torch, step, args.steps))
 
     # ---- per-kernel time with HIP events on the launch stream (separate pass) --------------
     for _ in range(args.calibrate_copy):
@@ -270,7 +355,7 @@ def main() -> int:
             acc[key] = acc.get(key, 0) + v
         for i in range(len(levels)):
             pl = binding.arrow_get_level_profile(op.h, i)
-            for cls in ("rows", "chunks", "reduce", "stage", "window", "panel"):
+            for cls in ("rows", "chunks", "reduce", "stage", "window", "panel", "corner"):
                 lev_acc[(cls, i)] = lev_acc.get((cls, i), 0.0) + pl[cls + "_ms"]
     binding.arrow_set_profiling(op.h, False)
     prof = {key: v / prof_runs for key, v in acc.items()}
@@ -282,20 +367,37 @@ def main() -> int:
     avg_ms = launch_ms[dom]
     bytes_per_launch = per_bytes[dom]
     achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
-    traffic = None
     kname = ("sddmm_" if sampled else "") + dom[0]
+    nnz_key = {"rows": "nnz_rows", "chunks": "nnz_chunks", "window": "nnz_window", "panel": "nnz_panel",
+               "corner": "nnz_corner"}.get(dom[0])
+    item_key = {"rows": "short_rows", "chunks": "chunks", "window": "window_rows", "panel": "panel_bins",
+                "corner": "corner_tiles"}.get(dom[0])
+    launch_nnz = levels[dom[1]][nnz_key] if nnz_key else 0
+    launch_items = levels[dom[1]][item_key] if item_key else 0
     tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{kname}_kernel_level{dom[1]}_{w.name}.json")
-    if os.path.exists(tpath):
-        with open(tpath) as f:
-            traffic = json.load(f).get("hbm_bytes_per_launch")
+    traffic, traffic_source = stored_traffic(tpath, launch_nnz, launch_items)
     roofline = {"bound": "hbm", "kernel": f"{kname}_kernel (level {dom[1]})", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": traffic, "avg_launch_ms": round(avg_ms, 4), "launches_per_step": 1,
-                "algorithmic_bytes_per_launch": int(bytes_per_launch)}
+                "traffic": traffic, "traffic_source": traffic_source,
+                "avg_launch_ms": round(avg_ms, 4), "launches_per_step": 1,
+                "algorithmic_bytes_per_launch": int(bytes_per_launch),
+                "launch": {"nnz": int(launch_nnz), "items": int(launch_items)}}
     if traffic and avg_ms > 0:
         # the counter bytes over the live launch time, and how much of them the method asks for
         roofline["counter_GBps"] = round(traffic / (avg_ms * 1e-3) / 1e9, 1)
         roofline["useful_fraction"] = round(bytes_per_launch / traffic, 4)
+    if not args.no_gather_yardstick:
+        # every stored entry of the launch gathers one row of 4k bytes: its rate against the bare
+        # gather of rows that all hit the L2 is how far the kernel is from the device's limit for
+        # this access pattern
+        yard = gather_yardstick(torch, binding, X, n, k, dev)
+        roofline["gather_yardstick"] = yard
+        if yard and avg_ms > 0 and launch_nnz:
+            rate = launch_nnz / (avg_ms * 1e-3) / 1e9
+            roofline["launch_Grows_per_s"] = round(rate, 2)
+            if yard.get("l2_hit_2MiB_per_die"):
+                roofline["frac_of_l2_hit_yardstick"] = round(rate / yard["l2_hit_2MiB_per_die"], 3)
+            roofline["product_Grows_per_s"] = round(nnz * l / (ms_per_step * 1e-3) / 1e9, 2)
 
     # ---- quick correctness sanity + CPU baseline: the oracle on a bounded row sample ----------
     cpu_baseline = None
@@ -366,11 +468,16 @@ def main() -> int:
                    else "fp32 A.X GFLOP/s (2*nnz*k), arrow-decomposed SpMM"),
         "value": round(gflops, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "scaling": None, "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "n": n, "nnz": nnz, "k": k, "b": w.b, "products": l,
                    "levels": op.info["levels"], "op": args.op, "tuning": {"kc": args.kc}},
+        "per_call_ms": per_call,
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
+        "levels": [{"n_i": L["n_i"], "nnz": L["nnz"], "nnz_head_head": L["nnz_head_head"],
+                    "nnz_head_row": L["nnz_head_row"], "nnz_head_col": L["nnz_head_col"], "nnz_diag": L["nnz_diag"],
+                    "blocks": L["blocks"], "separator_rule": L["separator_rule"], "nnz_fused": L["nnz_fused"],
+                    "nnz_corner": L["nnz_corner"]} for L in levels],
         "whole_path": {"algorithmic_GB": round(path_bytes / 1e9, 3),
                        "algorithmic_GBps": round(path_bytes * l / (ms_per_step * 1e-3) / 1e9, 1),
                        "frac_of_hbm_peak": round(path_bytes * l / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},

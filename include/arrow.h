@@ -328,6 +328,23 @@ int arrow_export_entry_map(const arrow_handle *h, uint32_t *out);
 int arrow_save(const arrow_handle *h, const char *path);
 int arrow_load(const char *path, arrow_handle **out);
 
+/*
+ * Measurement aid (no handle, not part of a product): a bare gather of whole rows, the yardstick
+ * the product kernels' gather rates are quoted against.  `gathers` pseudo-random rows (a fixed
+ * sequence) of the row-major fp32 matrix X (DEVICE, x_rows x k, 16-byte aligned) are read with one
+ * 16-byte load per lane, eight rows in flight per lane group, and summed.  The rows are drawn from
+ * the first region_rows rows of X; with per_die != 0 every accelerator die draws from a region of
+ * its own (die d: rows [d * region_rows, (d + 1) * region_rows)), so a small region stays in that
+ * die's L2; with from_lds != 0 the region (at most 64 KiB) is copied into LDS first and the rows
+ * are read from there.  k must be a power of two in [4, 256].  `out` (DEVICE, at least
+ * arrow_probe_gather_out_bytes(gathers) bytes) receives per-lane sums nobody needs.  Launches one
+ * kernel on `stream` and returns; the caller times it.
+ * Errors: EINVAL, ETOOSMALL, EHIP.
+ */
+size_t arrow_probe_gather_out_bytes(int64_t gathers);
+int arrow_probe_gather(const float *X, int64_t x_rows, int32_t k, int64_t region_rows, int32_t per_die,
+                       int32_t from_lds, int64_t gathers, float *out, size_t out_bytes, void *stream);
+
 /* Thread-local text of the last error ("" if none). Never NULL. */
 const char *arrow_last_error(void);
 

@@ -24,7 +24,7 @@ SYNTH_LIB = os.path.join(PKG_DIR, "synth", "libsynth.so")
 ORACLE_LIB = os.path.join(REPO_DIR, "oracle", "liboracle.so")
 
 HIP_SOURCES = ["csrc/decompose.cpp", "csrc/layout.cpp", "csrc/abi.cpp", "csrc/kernels.hip",
-               "csrc/csf3.cpp", "csrc/mttkrp.hip"]
+               "csrc/csf3.cpp", "csrc/mttkrp.hip", "csrc/probe.hip"]
 
 
 def _run(cmd: list[str]) -> None:

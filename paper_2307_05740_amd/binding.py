@@ -26,6 +26,7 @@ EXPORTED = [
     "arrow_sddmm_upload", "arrow_sddmm", "arrow_export_entry_map", "arrow_gather", "arrow_info",
     "arrow_level_info", "arrow_export_level", "arrow_self_check", "arrow_set_option", "arrow_set_profiling",
     "arrow_get_profile", "arrow_get_level_profile", "arrow_save", "arrow_load", "arrow_last_error",
+    "arrow_probe_gather", "arrow_probe_gather_out_bytes",
     "arrow_destroy",
     "csf3_build", "csf3_device_bytes", "csf3_upload", "csf3_workspace_bytes", "csf3_set_workspace",
     "csf3_mttkrp", "csf3_info", "csf3_set_profiling", "csf3_get_profile", "csf3_last_error", "csf3_destroy",
@@ -127,6 +128,10 @@ def lib():
     L.arrow_save.argtypes = [vp, ctypes.c_char_p]
     L.arrow_load.restype = ctypes.c_int
     L.arrow_load.argtypes = [ctypes.c_char_p, ctypes.POINTER(vp)]
+    L.arrow_probe_gather_out_bytes.restype = sz
+    L.arrow_probe_gather_out_bytes.argtypes = [i64]
+    L.arrow_probe_gather.restype = ctypes.c_int
+    L.arrow_probe_gather.argtypes = [vp, i64, i32, i64, i32, i32, i64, vp, sz, vp]
     L.arrow_last_error.restype = ctypes.c_char_p
     L.arrow_last_error.argtypes = []
     L.arrow_destroy.restype = None
@@ -289,6 +294,16 @@ def arrow_load(path: str) -> int:
     out = ctypes.c_void_p()
     _check(lib().arrow_load(os.fsencode(path), ctypes.byref(out)))
     return out.value
+
+
+def arrow_probe_gather_out_bytes(gathers: int) -> int:
+    return lib().arrow_probe_gather_out_bytes(gathers)
+
+
+def arrow_probe_gather(x_ptr: int, x_rows: int, k: int, region_rows: int, per_die: bool, from_lds: bool,
+                       gathers: int, out_ptr: int, out_bytes: int, stream: int = 0) -> None:
+    _check(lib().arrow_probe_gather(x_ptr, x_rows, k, region_rows, int(per_die), int(from_lds), gathers,
+                                    out_ptr, out_bytes, stream))
 
 
 def arrow_destroy(h: int) -> None:

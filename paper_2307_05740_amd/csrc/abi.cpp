@@ -614,6 +614,24 @@ int arrow_gather(arrow_handle* h, int32_t level, const float* X, float* Xp, int3
   return check_hip(rc, "gather kernel launch");
 }
 
+size_t arrow_probe_gather_out_bytes(int64_t gathers) {
+  return gathers < 1 ? 0 : sizeof(float) * (size_t)arrow::probe_out_floats(gathers);
+}
+
+int arrow_probe_gather(const float* X, int64_t x_rows, int32_t k, int64_t region_rows, int32_t per_die,
+                       int32_t from_lds, int64_t gathers, float* out, size_t out_bytes, void* stream) {
+  if (!X || !out) return fail(ARROW_EINVAL, "X or out is NULL");
+  if (((uintptr_t)X | (uintptr_t)out) % 16) return fail(ARROW_EINVAL, "X and out must be 16-byte aligned");
+  if (gathers < 1 || x_rows < 1) return fail(ARROW_EINVAL, "gathers and x_rows must be >= 1");
+  if (out_bytes < arrow_probe_gather_out_bytes(gathers))
+    return fail(ARROW_ETOOSMALL, "out needs %zu bytes", arrow_probe_gather_out_bytes(gathers));
+  int rc = arrow::launch_probe_gather(X, x_rows, k, region_rows, per_die, from_lds, gathers, out, stream);
+  if (rc == (int)hipErrorInvalidValue)
+    return fail(ARROW_EINVAL, "k must be a power of two in [4, 256]; the region (x 8 with per_die) must fit "
+                "into X, and into 64 KiB with from_lds");
+  return check_hip(rc, "gather probe launch");
+}
+
 int arrow_info(const arrow_handle* h, arrow_info_t* out) {
   if (!h || !out) return fail(ARROW_EINVAL, "NULL argument");
   out->n = h->n; out->nnz = h->nnz; out->b = h->b;

@@ -249,6 +249,13 @@ int launch_sddmm_chunks(const uint32_t* chunk_ptr, const uint32_t* chunk_mid, co
                         const float* V, int64_t v_rows, const float* Vh, float* S, int32_t k,
                         void* stream);
 
+// Bare row gather (probe.hip), the yardstick of the measurements: `gathers` pseudo-random rows of
+// the n x k matrix X drawn from its first region_rows rows (per_die: from a region of its own for
+// every accelerator die; from_lds: the region is copied into LDS first) are read and summed.
+int64_t probe_out_floats(int64_t gathers);
+int launch_probe_gather(const float* X, int64_t x_rows, int32_t k, int64_t region_rows, int per_die,
+                        int from_lds, int64_t gathers, float* out, void* stream);
+
 // Order-3 MTTKRP over the compressed-sparse-fibre image (mttkrp.hip): one wavefront per item.
 // b_rows, c_rows = rows of the factor matrices (they decide whether 32-bit offsets are enough);
 // mean_segment = entries per segment on average (it picks how many row loads a round issues).

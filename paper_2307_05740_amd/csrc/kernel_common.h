@@ -115,7 +115,7 @@ struct Shape {
   int vec, lpr, slices;
 };
 
-Shape pick_shape(int k, int kc) {
+[[maybe_unused]] Shape pick_shape(int k, int kc) {
   Shape s;
   s.vec = (k % 4 == 0) ? 4 : (k % 2 == 0) ? 2 : 1;
   int width = k;                                   // columns per slice

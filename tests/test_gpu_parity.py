@@ -550,3 +550,27 @@ def test_product_under_graph_capture(torch):
         Yref, B = oracle.spmm(*csr_of(w), Xs[t])
         assert_within(Yg, Yref, B)
     op.close()
+
+
+def test_gather_probe_runs_and_validates(torch):
+    """The bare row gather that bench.py uses as its yardstick: every mode launches and completes;
+    regions that do not fit, unsupported k and short output buffers are refused on the host."""
+    n, k = 1 << 16, 128
+    X = torch.ones((n, k), device="cuda")
+    gathers = 1 << 20
+    nbytes = binding.arrow_probe_gather_out_bytes(gathers)
+    out = torch.zeros(nbytes // 4, device="cuda")
+    for rows, per_die, lds in ((128, True, True), (4096, True, False), (n, False, False)):
+        binding.arrow_probe_gather(X.data_ptr(), n, k, rows, per_die, lds, gathers, out.data_ptr(), nbytes)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        # X is all ones: a lane sums 4 columns of the 2048 / 2 rows its lane group reads (16 times
+        # as many when the region sits in LDS, with 16 times fewer wavefronts)
+        reps = 16 if lds else 1
+        assert np.all(got[: (gathers // (2048 * reps)) * 64] == 4 * 1024 * reps)
+    for bad in (dict(k=24), dict(rows=n, per_die=True), dict(rows=256, lds=True), dict(nbytes=64)):
+        a = dict(k=k, rows=4096, per_die=False, lds=False, nbytes=nbytes)
+        a.update(bad)
+        with pytest.raises(binding.ArrowError):
+            binding.arrow_probe_gather(X.data_ptr(), n, a["k"], a["rows"], a["per_die"], a["lds"], gathers,
+                                       out.data_ptr(), a["nbytes"])
