@@ -227,7 +227,76 @@ int arrow_export_level(const arrow_handle *h, int32_t level, int32_t *perm,
 int arrow_self_check(const arrow_handle *h);
 
 /*
- * Launch-time tunables, by name:
+ * Every choice the decomposition, the packing of the device image and the launches leave open,
+ * as one plain struct.  arrow_options_default() fills it with the built-in defaults (given per
+ * field below) and then applies overrides from the environment: a variable ARROW_<FIELD NAME IN
+ * CAPITALS> holding a decimal integer replaces that field (the two ratios are given as
+ * ARROW_WINDOW_REUSE_X10 = 10 x window_reuse and ARROW_WINDOW_SHARE_X1000 = 1000 x
+ * window_level_share).  The environment is read by that one function and nowhere else; it exists
+ * for experiments and tests.  arrow_decompose(...) and arrow_load(...) are
+ * arrow_decompose_with(..., NULL, ...) and arrow_load_with(..., NULL, ...): NULL options mean
+ * "what arrow_options_default() returns now".
+ */
+typedef struct arrow_options_t {
+  /* --- decomposition (host) --- */
+  int32_t separators;     /* 1: try the block-separator rule before the plain top-degree head     */
+  int32_t bfs_tail;       /* 1: later levels / the body of a plain level are arranged by traversal */
+  int32_t head_by_id;     /* 1: head vertices of the plain rule in id order; 0: by falling degree  */
+  int64_t hubs_first;     /* 0: with head_by_id, this many highest degrees lead the head by falling
+                             degree (makes the top-left corner of the head block dense)            */
+  /* --- packing of the device image (host) --- */
+  int32_t short_max;      /* 16: rows with at most this many entries go to the lane-group list    */
+  int32_t chunk_nnz;      /* 256: most entries of a wavefront chunk                               */
+  int32_t chunk_min;      /* 64: column windows of a row are merged until a piece holds this many */
+  int32_t window_rows;    /* 4096: column positions per window of the chunk order (0 = row-major) */
+  int32_t classes;        /* 0: column classes of the die queues (rounded up to a multiple of 8)   */
+  int32_t class_gran;     /* 512: column positions dealt to a class at a time                     */
+  int32_t class_min;      /* 32: a row is split by class when it holds classes x this many entries */
+  int32_t piece_max;      /* 48: a piece of a long row with at most this many entries is a lane-group item */
+  int32_t stage_head;     /* 1: gather the head rows of level 0 into a contiguous buffer per product */
+  int32_t stage_short;    /* -1: short rows read head columns from that buffer when the head is
+                             scattered over X; 1 / 0: always / never                               */
+  int32_t empty_last;     /* 1: level-0 rows without entries are listed after all other short rows */
+  int32_t panel;          /* 0: head panels (128 head rows per group, accumulators in LDS, one column
+                             class per accelerator die) for head rows with few entries per window  */
+  int32_t panel_min;      /* 8: fewest head-block entries of a row that joins a panel             */
+  int32_t window_span;    /* 2048: widest column span of a diagonal-block tile whose window of
+                             P_i X is staged in LDS (at most 4096; 0 = no such tiles)               */
+  int32_t window_tile_rows; /* 1024: most rows of such a tile                                      */
+  double window_reuse;    /* 8.0: a tile is kept when its diagonal-block entries >= this x its span */
+  double window_level_share; /* 0.05: ... and the tiles of a level when they hold this share of it */
+  int32_t fuse_levels;    /* 1: the entries later levels hold for a vertex are listed with its
+                             level-0 row: one item sums over all arrow matrices, later levels need
+                             neither launches nor a read-modify-write of Y; 0: one launch set per level */
+  int32_t corner;         /* 0: 1 = rows and columns [0, S) of the head block of level 0 run in tiles
+                             of 256 x 256 with staged head rows and accumulators in LDS              */
+  int32_t corner_max;     /* 65536: largest S considered                                          */
+  int32_t corner_min_tile;/* 768: S is the largest multiple of 256 whose outermost band of tiles
+                             holds this many entries per tile on average                            */
+  /* --- launches (may also be changed later with arrow_set_option) --- */
+  int32_t kc;             /* 0 = automatic (64 when the head is staged and k > 64, else the whole
+                             row up to 256 columns): columns per pass of the chunk kernel           */
+  int64_t l2_resident_bytes; /* 2 MiB: share of a die's L2 a resident slice of the staged head may
+                             take when kc is chosen automatically with die queues                   */
+} arrow_options_t;
+
+/* Built-in defaults, then the ARROW_* environment overrides described above. NULL is ignored. */
+void arrow_options_default(arrow_options_t *opt);
+
+/*
+ * arrow_decompose / arrow_load with explicit options (opt == NULL: arrow_options_default()).
+ * arrow_repack rebuilds the device image of an existing handle with other packing and launch
+ * options (the decomposition fields are ignored: the levels stay as they are); the handle is
+ * unbound from its device image and workspace and needs arrow_upload and arrow_set_workspace
+ * again.  Errors as arrow_decompose / arrow_load.
+ */
+int arrow_decompose_with(int64_t n, const int64_t *rowptr, const int32_t *colidx, const float *vals,
+                         int32_t b, const arrow_options_t *opt, arrow_handle **out);
+int arrow_load_with(const char *path, const arrow_options_t *opt, arrow_handle **out);
+int arrow_repack(arrow_handle *h, const arrow_options_t *opt);
+
+/*
+ * Launch-time tunables of an existing handle, by name:
  *   "kc"        columns per pass of the chunk kernel; a smaller slice shrinks the working set of
  *               X rows per pass and re-reads the entries k/kc times.  0 = automatic: 64 when the
  *               head is staged and k > 64, the whole row (up to 256 columns) otherwise
@@ -236,42 +305,6 @@ int arrow_self_check(const arrow_handle *h);
  *   "sddmm_image_order"  1: arrow_sddmm writes S in the order of the packed image instead of the
  *               caller's CSR order (contiguous stores; arrow_export_entry_map tells which nonzero
  *               each element belongs to); default 0
- * Pack-time choices are read from the environment by arrow_decompose: ARROW_SHORT_MAX (rows
- * with at most this many entries are handled one per lane group, default 16), ARROW_CHUNK_NNZ
- * (most entries per wavefront chunk, default 256), ARROW_WINDOW_ROWS (long rows are cut at
- * multiples of this many column positions and their chunks run window by window, default 4096,
- * 0 = plain row-major chunks), ARROW_CHUNK_MIN (windows of a row are merged until a chunk
- * holds this many entries, default 64), ARROW_CLASSES (column classes of the die queues, a
- * multiple of 8, default 0 = none), ARROW_CLASS_GRAN (column positions dealt to a class at a time,
- * default 512), ARROW_CLASS_MIN (a row is split by class when it holds classes x this many
- * entries, default 32), ARROW_PIECE_MAX (a class piece or window piece of a long row with at most
- * this many entries is handled by a lane group instead of a wavefront, default 48), ARROW_STAGE_HEAD (1: the head rows of level 0 are gathered into a
- * contiguous buffer before the product), ARROW_STAGE_SHORT (1 / 0: the short rows read their head
- * columns from that buffer as well / from X; default -1 = from the buffer when the head vertices are
- * scattered over X), ARROW_EMPTY_LAST (1, the default: the rows of level 0 without entries, which only
- * store zeros, are listed after all other short rows), ARROW_WINDOW_SPAN (widest column span of a diagonal-block tile whose
- * window of P_i X is staged in LDS, default 2048, at most 4096, 0 = no such tiles),
- * ARROW_WINDOW_TILE_ROWS (most rows per tile, default 1024), ARROW_WINDOW_REUSE_X10 (a tile is
- * kept when its diagonal-block entries number at least this / 10 times its span, default 80),
- * ARROW_WINDOW_SHARE_X1000 (the tiles of a level are kept when they hold at least this / 1000 of
- * the level's entries, default 50),
- * ARROW_PANEL (1: head rows of level 0 with few entries per column window run their head-block
- * entries in panels: 128 rows per group, one workgroup per group and column class with the
- * group's accumulators in LDS, class c served by accelerator die c; default 0), ARROW_PANEL_MIN
- * (fewest head-block entries of a row that joins a panel, default 8),
- * ARROW_FUSE_LEVELS (1, the default: the entries that later levels hold for a vertex are listed
- * with the vertex's level-0 row, so one item sums over all arrow matrices and the later levels
- * need neither launches nor a read-modify-write of Y; 0: every level runs its own launches),
- * ARROW_CORNER (1: when the head of level 0 is staged, the dense top-left corner of
- * the head block -- rows and columns [0, S) -- runs in tiles of 256 x 256 with the tile's staged
- * head rows and the row panel's accumulators in LDS; S is the largest multiple of 256 up to
- * ARROW_CORNER_MAX, default 65536, whose outermost band of tiles holds at least
- * ARROW_CORNER_MIN_TILE, default 768, entries per tile on average; default 0: no corner; meant to
- * be used with ARROW_HUBS_FIRST, which makes that corner dense),
- * ARROW_SEPARATORS and ARROW_BFS_TAIL (0 disables the separator rule / the breadth-first
- * arrangement of later levels), ARROW_HEAD_BY_ID (1, the default: the head vertices of the plain
- * rule sit in id order inside the head, after the ARROW_HUBS_FIRST, default 0, highest degrees,
- * which lead the head by falling degree and make its top-left corner dense; 0: all by falling degree).
  * Errors: EINVAL (unknown name, value out of range).
  */
 int arrow_set_option(arrow_handle *h, const char *name, int64_t value);
@@ -317,10 +350,11 @@ int arrow_export_entry_map(const arrow_handle *h, uint32_t *out);
 
 /*
  * Persistence (host only).  arrow_save writes the arrow matrices of a handle (permutations and
- * the entries of every B_i with their indices in the caller's CSR arrays, not the device image) to `path`; arrow_load reads such a file, checks
- * it (sizes, injective permutations, ordered in-range column positions, arrow shape of width b,
- * entry count, source indices a bijection onto the nonzeros) and rebuilds the device image with the pack-time choices of the CURRENT
- * environment, so a decomposition is paid once per operand.  The loaded handle behaves like one
+ * the entries of every B_i with their indices in the caller's CSR arrays, not the device image)
+ * to `path`; arrow_load reads such a file, checks it (sizes, injective permutations, ordered
+ * in-range column positions, arrow shape of width b, entry count, source indices a bijection onto
+ * the nonzeros) and rebuilds the device image with the loader's packing options
+ * (arrow_load_with), so a decomposition is paid once per operand.  The loaded handle behaves like one
  * from arrow_decompose (it still needs arrow_upload and a workspace).
  * Errors: EINVAL (NULL, file cannot be opened / written, not a level file, truncated, fails a
  * check), ENOMEM.

@@ -27,6 +27,7 @@ EXPORTED = [
     "arrow_level_info", "arrow_export_level", "arrow_self_check", "arrow_set_option", "arrow_set_profiling",
     "arrow_get_profile", "arrow_get_level_profile", "arrow_save", "arrow_load", "arrow_last_error",
     "arrow_probe_gather", "arrow_probe_gather_out_bytes",
+    "arrow_options_default", "arrow_decompose_with", "arrow_load_with", "arrow_repack",
     "arrow_destroy",
     "csf3_build", "csf3_device_bytes", "csf3_upload", "csf3_workspace_bytes", "csf3_set_workspace",
     "csf3_mttkrp", "csf3_info", "csf3_set_profiling", "csf3_get_profile", "csf3_last_error", "csf3_destroy",
@@ -54,6 +55,18 @@ class arrow_level_info_t(ctypes.Structure):
                [("blocks", ctypes.c_int32), ("separator_rule", ctypes.c_int32), ("nnz_fused", ctypes.c_int64),
                 ("corner", ctypes.c_int64), ("corner_tiles", ctypes.c_int64), ("corner_items", ctypes.c_int64),
                 ("nnz_corner", ctypes.c_int64)]
+
+
+class arrow_options_t(ctypes.Structure):
+    _fields_ = [("separators", ctypes.c_int32), ("bfs_tail", ctypes.c_int32), ("head_by_id", ctypes.c_int32),
+                ("hubs_first", ctypes.c_int64)] + \
+               [(name, ctypes.c_int32) for name in
+                ("short_max", "chunk_nnz", "chunk_min", "window_rows", "classes", "class_gran", "class_min",
+                 "piece_max", "stage_head", "stage_short", "empty_last", "panel", "panel_min", "window_span",
+                 "window_tile_rows")] + \
+               [("window_reuse", ctypes.c_double), ("window_level_share", ctypes.c_double)] + \
+               [(name, ctypes.c_int32) for name in ("fuse_levels", "corner", "corner_max", "corner_min_tile", "kc")] + \
+               [("l2_resident_bytes", ctypes.c_int64)]
 
 
 class arrow_profile_t(ctypes.Structure):
@@ -132,6 +145,14 @@ def lib():
     L.arrow_probe_gather_out_bytes.argtypes = [i64]
     L.arrow_probe_gather.restype = ctypes.c_int
     L.arrow_probe_gather.argtypes = [vp, i64, i32, i64, i32, i32, i64, vp, sz, vp]
+    L.arrow_options_default.restype = None
+    L.arrow_options_default.argtypes = [ctypes.POINTER(arrow_options_t)]
+    L.arrow_decompose_with.restype = ctypes.c_int
+    L.arrow_decompose_with.argtypes = [i64, vp, vp, vp, i32, ctypes.POINTER(arrow_options_t), ctypes.POINTER(vp)]
+    L.arrow_load_with.restype = ctypes.c_int
+    L.arrow_load_with.argtypes = [ctypes.c_char_p, ctypes.POINTER(arrow_options_t), ctypes.POINTER(vp)]
+    L.arrow_repack.restype = ctypes.c_int
+    L.arrow_repack.argtypes = [vp, ctypes.POINTER(arrow_options_t)]
     L.arrow_last_error.restype = ctypes.c_char_p
     L.arrow_last_error.argtypes = []
     L.arrow_destroy.restype = None
@@ -182,6 +203,42 @@ def arrow_decompose(rowptr: np.ndarray, colidx: np.ndarray, vals: np.ndarray, b:
     _check(lib().arrow_decompose(n, rowptr.ctypes.data, colidx.ctypes.data, vals.ctypes.data, b,
                                  ctypes.byref(out)))
     return out.value
+
+
+def arrow_options_default(**overrides) -> arrow_options_t:
+    """The library's default options (built-in values, then ARROW_* environment overrides), with
+    the given fields replaced."""
+    opt = arrow_options_t()
+    lib().arrow_options_default(ctypes.byref(opt))
+    names = {f for f, _ in arrow_options_t._fields_}
+    for name, value in overrides.items():
+        if name not in names:
+            raise KeyError(f"arrow_options_t has no field {name!r}")
+        setattr(opt, name, value)
+    return opt
+
+
+def arrow_decompose_with(rowptr: np.ndarray, colidx: np.ndarray, vals: np.ndarray, b: int,
+                         opt: arrow_options_t | None, n: int | None = None) -> int:
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
+    colidx = np.ascontiguousarray(colidx, dtype=np.int32)
+    vals = np.ascontiguousarray(vals, dtype=np.float32)
+    n = rowptr.shape[0] - 1 if n is None else n
+    out = ctypes.c_void_p()
+    _check(lib().arrow_decompose_with(n, rowptr.ctypes.data, colidx.ctypes.data, vals.ctypes.data, b,
+                                      ctypes.byref(opt) if opt is not None else None, ctypes.byref(out)))
+    return out.value
+
+
+def arrow_load_with(path: str, opt: arrow_options_t | None) -> int:
+    out = ctypes.c_void_p()
+    _check(lib().arrow_load_with(os.fsencode(path), ctypes.byref(opt) if opt is not None else None,
+                                 ctypes.byref(out)))
+    return out.value
+
+
+def arrow_repack(h: int, opt: arrow_options_t | None) -> None:
+    _check(lib().arrow_repack(h, ctypes.byref(opt) if opt is not None else None))
 
 
 def arrow_device_bytes(h: int) -> int:
@@ -313,13 +370,18 @@ def arrow_destroy(h: int) -> None:
 class ArrowSpMM:
     """One decomposed operand bound to torch-owned device memory (plumbing only)."""
 
-    def __init__(self, rowptr=None, colidx=None, vals=None, b: int = 0, device="cuda:0", handle=None):
+    def __init__(self, rowptr=None, colidx=None, vals=None, b: int = 0, device="cuda:0", handle=None,
+                 options: arrow_options_t | None = None):
         import torch
         self._torch = torch
         self.device = torch.device(device)
-        self.h = handle if handle is not None else arrow_decompose(rowptr, colidx, vals, b)
+        self.h = handle if handle is not None else arrow_decompose_with(rowptr, colidx, vals, b, options)
         self.info = arrow_info(self.h)
         self.n = self.info["n"]
+        self._bind_image()
+
+    def _bind_image(self) -> None:
+        torch = self._torch
         nbytes = arrow_device_bytes(self.h)
         with torch.cuda.device(self.device):
             self._image = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
@@ -328,6 +390,12 @@ class ArrowSpMM:
         self._ws = None
         self._ws_k = 0
         self._map = None
+
+    def repack(self, options: arrow_options_t | None) -> None:
+        """Rebuild the device image with other packing / launch options and bind it again."""
+        self._torch.cuda.synchronize(self.device)
+        arrow_repack(self.h, options)
+        self._bind_image()
 
     def _stream(self) -> int:
         return self._torch.cuda.current_stream(self.device).cuda_stream

@@ -328,32 +328,25 @@ int sampled_product(arrow_handle* h, const float* U, const float* V, float* S_ou
   return ARROW_OK;
 }
 
-// pack-time and launch-time choices from the environment (see arrow_set_option in arrow.h)
-void read_pack_options(arrow_handle* h) {
-  h->pack.short_max = (int32_t)env_int("ARROW_SHORT_MAX", h->pack.short_max);
-  h->pack.chunk_nnz = (int32_t)env_int("ARROW_CHUNK_NNZ", h->pack.chunk_nnz);
-  h->pack.chunk_min = (int32_t)env_int("ARROW_CHUNK_MIN", h->pack.chunk_min);
-  h->pack.window_rows = (int32_t)env_int("ARROW_WINDOW_ROWS", h->pack.window_rows);
-  h->pack.classes = (int32_t)env_int("ARROW_CLASSES", h->pack.classes);
-  h->pack.class_gran = (int32_t)env_int("ARROW_CLASS_GRAN", h->pack.class_gran);
-  h->pack.class_min = (int32_t)env_int("ARROW_CLASS_MIN", h->pack.class_min);
-  h->pack.piece_max = (int32_t)env_int("ARROW_PIECE_MAX", h->pack.piece_max);
-  h->pack.stage_head = (int32_t)env_int("ARROW_STAGE_HEAD", h->pack.stage_head);
-  h->pack.stage_short = (int32_t)env_int("ARROW_STAGE_SHORT", h->pack.stage_short);
-  h->pack.empty_last = (int32_t)env_int("ARROW_EMPTY_LAST", h->pack.empty_last);
-  h->pack.fuse_levels = (int32_t)env_int("ARROW_FUSE_LEVELS", h->pack.fuse_levels);
-  h->pack.corner = (int32_t)env_int("ARROW_CORNER", h->pack.corner);
-  h->pack.corner_max = (int32_t)env_int("ARROW_CORNER_MAX", h->pack.corner_max);
-  h->pack.corner_min_tile = (int32_t)env_int("ARROW_CORNER_MIN_TILE", h->pack.corner_min_tile);
-  h->pack.panel = (int32_t)env_int("ARROW_PANEL", h->pack.panel);
-  h->pack.panel_min = (int32_t)env_int("ARROW_PANEL_MIN", h->pack.panel_min);
-  h->pack.window_span = (int32_t)env_int("ARROW_WINDOW_SPAN", h->pack.window_span);
-  if (h->pack.window_span > 4096) h->pack.window_span = 4096;   // 4096 positions x 4 columns x 4 B = 64 KiB of LDS
-  h->pack.window_tile_rows = (int32_t)env_int("ARROW_WINDOW_TILE_ROWS", h->pack.window_tile_rows);
-  h->pack.window_level_share = (double)env_int("ARROW_WINDOW_SHARE_X1000", (int64_t)(h->pack.window_level_share * 1000)) / 1000.0;
-  h->pack.window_reuse = (double)env_int("ARROW_WINDOW_REUSE_X10", (int64_t)(h->pack.window_reuse * 10)) / 10.0;
-  h->tuning.l2_resident_bytes = env_int("ARROW_L2_RESIDENT_BYTES", h->tuning.l2_resident_bytes);
-  h->tuning.kc = (int32_t)env_int("ARROW_KC", 0);
+// options struct -> the internal option sets of a handle
+void apply_options(arrow_handle* h, const arrow_options_t& o, arrow::DecomposeOptions* dopt) {
+  if (dopt) {
+    dopt->separators = o.separators != 0;
+    dopt->bfs_tail = o.bfs_tail != 0;
+    dopt->head_by_id = o.head_by_id != 0;
+    dopt->hubs_first = o.hubs_first;
+  }
+  arrow::PackOptions& p = h->pack;
+  p.short_max = o.short_max; p.chunk_nnz = o.chunk_nnz; p.chunk_min = o.chunk_min;
+  p.window_rows = o.window_rows; p.classes = o.classes; p.class_gran = o.class_gran;
+  p.class_min = o.class_min; p.piece_max = o.piece_max; p.stage_head = o.stage_head;
+  p.stage_short = o.stage_short; p.empty_last = o.empty_last; p.panel = o.panel; p.panel_min = o.panel_min;
+  p.window_span = o.window_span > 4096 ? 4096 : o.window_span;   // 4096 positions x 4 columns x 4 B = 64 KiB of LDS
+  p.window_tile_rows = o.window_tile_rows; p.window_reuse = o.window_reuse;
+  p.window_level_share = o.window_level_share; p.fuse_levels = o.fuse_levels;
+  p.corner = o.corner; p.corner_max = o.corner_max; p.corner_min_tile = o.corner_min_tile;
+  h->tuning.kc = o.kc < 0 ? 0 : (o.kc > 256 ? 256 : o.kc);
+  h->tuning.l2_resident_bytes = o.l2_resident_bytes < 0 ? 0 : o.l2_resident_bytes;
 }
 
 int ready(const arrow_handle* h, int32_t k, bool need_iter_buffer) {
@@ -424,8 +417,48 @@ extern "C" {
 
 const char* arrow_last_error(void) { return g_err.c_str(); }
 
+void arrow_options_default(arrow_options_t* o) {
+  if (!o) return;
+  const arrow::DecomposeOptions d;
+  const arrow::PackOptions p;
+  const arrow::LaunchTuning t;
+  // the one place that reads the environment: ARROW_<FIELD> overrides the built-in default
+  o->separators = (int32_t)env_int("ARROW_SEPARATORS", d.separators);
+  o->bfs_tail = (int32_t)env_int("ARROW_BFS_TAIL", d.bfs_tail);
+  o->head_by_id = (int32_t)env_int("ARROW_HEAD_BY_ID", d.head_by_id);
+  o->hubs_first = env_int("ARROW_HUBS_FIRST", d.hubs_first);
+  o->short_max = (int32_t)env_int("ARROW_SHORT_MAX", p.short_max);
+  o->chunk_nnz = (int32_t)env_int("ARROW_CHUNK_NNZ", p.chunk_nnz);
+  o->chunk_min = (int32_t)env_int("ARROW_CHUNK_MIN", p.chunk_min);
+  o->window_rows = (int32_t)env_int("ARROW_WINDOW_ROWS", p.window_rows);
+  o->classes = (int32_t)env_int("ARROW_CLASSES", p.classes);
+  o->class_gran = (int32_t)env_int("ARROW_CLASS_GRAN", p.class_gran);
+  o->class_min = (int32_t)env_int("ARROW_CLASS_MIN", p.class_min);
+  o->piece_max = (int32_t)env_int("ARROW_PIECE_MAX", p.piece_max);
+  o->stage_head = (int32_t)env_int("ARROW_STAGE_HEAD", p.stage_head);
+  o->stage_short = (int32_t)env_int("ARROW_STAGE_SHORT", p.stage_short);
+  o->empty_last = (int32_t)env_int("ARROW_EMPTY_LAST", p.empty_last);
+  o->panel = (int32_t)env_int("ARROW_PANEL", p.panel);
+  o->panel_min = (int32_t)env_int("ARROW_PANEL_MIN", p.panel_min);
+  o->window_span = (int32_t)env_int("ARROW_WINDOW_SPAN", p.window_span);
+  o->window_tile_rows = (int32_t)env_int("ARROW_WINDOW_TILE_ROWS", p.window_tile_rows);
+  o->window_reuse = (double)env_int("ARROW_WINDOW_REUSE_X10", (int64_t)(p.window_reuse * 10)) / 10.0;
+  o->window_level_share = (double)env_int("ARROW_WINDOW_SHARE_X1000", (int64_t)(p.window_level_share * 1000)) / 1000.0;
+  o->fuse_levels = (int32_t)env_int("ARROW_FUSE_LEVELS", p.fuse_levels);
+  o->corner = (int32_t)env_int("ARROW_CORNER", p.corner);
+  o->corner_max = (int32_t)env_int("ARROW_CORNER_MAX", p.corner_max);
+  o->corner_min_tile = (int32_t)env_int("ARROW_CORNER_MIN_TILE", p.corner_min_tile);
+  o->kc = (int32_t)env_int("ARROW_KC", t.kc);
+  o->l2_resident_bytes = env_int("ARROW_L2_RESIDENT_BYTES", t.l2_resident_bytes);
+}
+
 int arrow_decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, const float* vals,
                     int32_t b, arrow_handle** out) {
+  return arrow_decompose_with(n, rowptr, colidx, vals, b, nullptr, out);
+}
+
+int arrow_decompose_with(int64_t n, const int64_t* rowptr, const int32_t* colidx, const float* vals,
+                         int32_t b, const arrow_options_t* opt, arrow_handle** out) {
   if (!out) return fail(ARROW_EINVAL, "out is NULL");
   *out = nullptr;
   if (n < 1 || n > 2147483646LL) return fail(ARROW_EINVAL, "n must be in [1, 2^31 - 2] (got %lld)", (long long)n);
@@ -457,11 +490,9 @@ int arrow_decompose(int64_t n, const int64_t* rowptr, const int32_t* colidx, con
   if (!h) return fail(ARROW_ENOMEM, "out of host memory");
   h->n = n; h->nnz = nnz; h->b = b;
   arrow::DecomposeOptions dopt;
-  dopt.separators = env_int("ARROW_SEPARATORS", 1) != 0;
-  dopt.bfs_tail = env_int("ARROW_BFS_TAIL", 1) != 0;
-  dopt.head_by_id = env_int("ARROW_HEAD_BY_ID", 1) != 0;
-  dopt.hubs_first = env_int("ARROW_HUBS_FIRST", dopt.hubs_first);
-  read_pack_options(h);
+  arrow_options_t defaults;
+  if (!opt) { arrow_options_default(&defaults); opt = &defaults; }
+  apply_options(h, *opt, &dopt);
   std::string err;
   int rc;
   try {
@@ -763,7 +794,27 @@ int arrow_save(const arrow_handle* h, const char* path) {
   return ARROW_OK;
 }
 
-int arrow_load(const char* path, arrow_handle** out) {
+int arrow_load(const char* path, arrow_handle** out) { return arrow_load_with(path, nullptr, out); }
+
+int arrow_repack(arrow_handle* h, const arrow_options_t* opt) {
+  if (!h) return fail(ARROW_EINVAL, "handle is NULL");
+  arrow_options_t defaults;
+  if (!opt) { arrow_options_default(&defaults); opt = &defaults; }
+  apply_options(h, *opt, nullptr);
+  h->dev = nullptr; h->ws = nullptr; h->ws_bytes = 0; h->dev_map = nullptr;
+  std::string err;
+  int rc;
+  try {
+    rc = arrow::pack_image(h->n, h->b, h->levels, h->pack, h->img, err);
+  } catch (const std::bad_alloc&) {
+    rc = ARROW_ENOMEM;
+    err = "out of host memory while packing";
+  }
+  if (rc != ARROW_OK) return fail(rc, "%s", err.c_str());
+  return ARROW_OK;
+}
+
+int arrow_load_with(const char* path, const arrow_options_t* opt, arrow_handle** out) {
   if (!out) return fail(ARROW_EINVAL, "out is NULL");
   *out = nullptr;
   if (!path) return fail(ARROW_EINVAL, "path is NULL");
@@ -803,7 +854,9 @@ int arrow_load(const char* path, arrow_handle** out) {
     f = nullptr;
     if (ok) ok = levels_valid(h->n, h->nnz, h->b, h->levels, why);
     if (!ok) { delete h; return fail(ARROW_EINVAL, "'%s': %s", path, why.c_str()); }
-    read_pack_options(h);
+    arrow_options_t defaults;
+    if (!opt) { arrow_options_default(&defaults); opt = &defaults; }
+    apply_options(h, *opt, nullptr);
     std::string err;
     auto t0 = std::chrono::steady_clock::now();
     int rc = arrow::pack_image(h->n, h->b, h->levels, h->pack, h->img, err);

@@ -52,8 +52,12 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
   const int64_t it = (int64_t)blockIdx.x * WPB + wave;
   if (it >= n_items) return;            // whole wavefront leaves together
   const uint32_t s_lo = item_seg[it], e_lo = item_ent[it];
-  const uint32_t n_seg = item_seg[it + 1] - s_lo, n_ent = item_ent[it + 1] - e_lo;
-  if (n_seg > (uint32_t)kCsfItemSegs || n_ent > (uint32_t)kCsfItemNnz) return;   // never true for a built image
+  uint32_t n_seg = item_seg[it + 1] - s_lo, n_ent = item_ent[it + 1] - e_lo;
+  // An item beyond what the staging arrays hold cannot come out of csf3_build, which is the one
+  // place that enforces the limits; if an image ever carried one, its destination row is filled
+  // with NaN (a result that announces itself) instead of being left with whatever it held.
+  const bool over_limit = n_seg > (uint32_t)kCsfItemSegs || n_ent > (uint32_t)kCsfItemNnz;
+  if (over_limit) { n_seg = 0; n_ent = 0; }
   const int lane = threadIdx.x % 64;
   const int g = lane / LPR;
   const int c = (lane % LPR) * VEC + blockIdx.y * (LPR * VEC);
@@ -88,6 +92,7 @@ __global__ __launch_bounds__(kBlock) void mttkrp_kernel(
   }
 #pragma unroll
   for (int m = LPR; m < 64; m <<= 1) vadd(acc, vshfl_xor(acc, m));
+  if (over_limit) vfma(acc, __builtin_nanf(""), acc);
   if (g == 0 && col_ok) {
     const int32_t dst = item_dst[it];
     if (dst >= 0) vstore<VEC>(A + (size_t)dst * (size_t)R + c, acc);

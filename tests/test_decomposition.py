@@ -608,6 +608,56 @@ def test_save_and_load_round_trip(tmp_path, monkeypatch):
         binding.arrow_load(str(tmp_path / "does_not_exist"))
 
 
+def test_explicit_options_replace_the_environment(monkeypatch):
+    """Options are an argument: the struct arrow_options_default() returns carries the built-in
+    defaults plus ARROW_* overrides, and what a call receives is all that counts."""
+    for name in list(os.environ):
+        if name.startswith("ARROW_"):
+            monkeypatch.delenv(name)
+    d = binding.arrow_options_default()
+    assert (d.separators, d.bfs_tail, d.head_by_id, d.hubs_first) == (1, 1, 1, 0)
+    assert (d.short_max, d.chunk_nnz, d.chunk_min, d.window_rows, d.piece_max) == (16, 256, 64, 4096, 48)
+    assert (d.fuse_levels, d.corner, d.panel, d.classes, d.kc) == (1, 0, 0, 0, 0)
+    assert d.window_reuse == 8.0 and d.window_level_share == 0.05 and d.l2_resident_bytes == 2 << 20
+    monkeypatch.setenv("ARROW_CHUNK_NNZ", "32")
+    monkeypatch.setenv("ARROW_WINDOW_REUSE_X10", "25")
+    e = binding.arrow_options_default(short_max=3)
+    assert e.chunk_nnz == 32 and e.window_reuse == 2.5 and e.short_max == 3
+    with pytest.raises(KeyError):
+        binding.arrow_options_default(no_such_field=1)
+    w = synth.make_config(0)
+    # explicit options win over the environment; NULL options take the environment
+    h_env = binding.arrow_decompose(w.rowptr, w.colidx, w.vals, w.b)
+    h_opt = binding.arrow_decompose_with(w.rowptr, w.colidx, w.vals, w.b, d)
+    h_sep = binding.arrow_decompose_with(w.rowptr, w.colidx, w.vals, w.b,
+                                         binding.arrow_options_default(fuse_levels=0, chunk_nnz=256))
+    try:
+        for h in (h_env, h_opt, h_sep):
+            binding.arrow_self_check(h)
+        c_env, c_opt = (binding.arrow_level_info(h, 0)["chunks"] for h in (h_env, h_opt))
+        assert c_env > c_opt                              # chunks of 32 against chunks of 256
+        assert binding.arrow_level_info(h_opt, 0)["nnz_fused"] > 0
+        assert binding.arrow_level_info(h_sep, 0)["nnz_fused"] == 0
+        # repacking changes the image, not the levels
+        before = [binding.arrow_export_level(h_opt, i) for i in range(binding.arrow_info(h_opt)["levels"])]
+        binding.arrow_repack(h_opt, binding.arrow_options_default(chunk_nnz=64, fuse_levels=0, corner=1,
+                                                                  corner_min_tile=1))
+        binding.arrow_self_check(h_opt)
+        li = binding.arrow_level_info(h_opt, 0)
+        assert li["nnz_fused"] == 0 and li["nnz_corner"] > 0 and li["chunks"] != c_opt
+        after = [binding.arrow_export_level(h_opt, i) for i in range(binding.arrow_info(h_opt)["levels"])]
+        for a, c in zip(before, after):
+            for x, y in zip(a, c):
+                assert np.array_equal(x.view(np.uint32) if x.dtype == np.float32 else x,
+                                      y.view(np.uint32) if y.dtype == np.float32 else y)
+        with pytest.raises(binding.ArrowError) as ei:     # the old device image is no longer bound
+            binding.arrow_spmm(h_opt, 4096, 1 << 20, 4)
+        assert ei.value.code == binding.ARROW_ENOTREADY
+    finally:
+        for h in (h_env, h_opt, h_sep):
+            binding.arrow_destroy(h)
+
+
 def test_library_exports_every_declared_symbol():
     import glob
     import re

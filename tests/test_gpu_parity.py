@@ -574,3 +574,22 @@ def test_gather_probe_runs_and_validates(torch):
         with pytest.raises(binding.ArrowError):
             binding.arrow_probe_gather(X.data_ptr(), n, a["k"], a["rows"], a["per_die"], a["lds"], gathers,
                                        out.data_ptr(), a["nbytes"])
+
+
+def test_explicit_options_and_repack(torch):
+    """Options passed as a struct instead of through the environment, and an image rebuilt on the
+    same handle with other options: every variant within the oracle's bound."""
+    w = synth.make_config(3, shrink=8)
+    X = synth.normal_matrix(w.n, 36, seed=77)
+    Yref, B = oracle.spmm(*csr_of(w), X)
+    Xd = torch.from_numpy(X).cuda()
+    op = binding.ArrowSpMM(*csr_of(w), w.b, options=binding.arrow_options_default(hubs_first=65536, chunk_nnz=100))
+    assert_within(op.spmm(Xd).cpu().numpy(), Yref, B)
+    for kw in (dict(corner=1), dict(fuse_levels=0, short_max=4), dict(panel=1, window_rows=64),
+               dict(classes=8, class_min=2, class_gran=16, kc=16), dict()):
+        op.repack(binding.arrow_options_default(**kw))
+        lv = op.levels()
+        assert (lv[0]["nnz_corner"] > 0) == bool(kw.get("corner")) and (lv[0]["nnz_panel"] > 0) == bool(kw.get("panel"))
+        Yd = torch.full_like(Xd, float("nan"))
+        assert_within(op.spmm(Xd, Yd).cpu().numpy(), Yref, B)
+    op.close()
