@@ -6,6 +6,10 @@ Three independent shared objects are produced:
 * ``paper_2307_05740_amd/synth/libsynth.so``  -- seeded input generators (gcc)
 * ``oracle/liboracle.so``                     -- the fp64 CPU checker (gcc); building it is not using it
 
+``python -m paper_2307_05740_amd._build arrow --sanitize`` builds ``arrow_host_check_asan``
+instead: the host half of the library (everything but the kernels) as a CPU-only program under
+AddressSanitizer and UndefinedBehaviorSanitizer; ``tests/test_host_sanitizer.py`` runs it.
+
 Nothing here is run at import time; ``__graft_entry__.build()`` and the
 ``python -m paper_2307_05740_amd._build`` command line call it.
 """
@@ -24,7 +28,7 @@ SYNTH_LIB = os.path.join(PKG_DIR, "synth", "libsynth.so")
 ORACLE_LIB = os.path.join(REPO_DIR, "oracle", "liboracle.so")
 
 HIP_SOURCES = ["csrc/decompose.cpp", "csrc/layout.cpp", "csrc/abi.cpp", "csrc/kernels.hip",
-               "csrc/csf3.cpp", "csrc/mttkrp.hip", "csrc/probe.hip"]
+               "csrc/csf3.cpp", "csrc/mttkrp.hip", "csrc/probe.hip", "csrc/static_scratch.hip"]
 
 
 def _run(cmd: list[str]) -> None:
@@ -72,6 +76,26 @@ def build_arrow() -> str:
     return ARROW_LIB
 
 
+HOST_CHECK = os.path.join(PKG_DIR, "arrow_host_check")
+HOST_SOURCES = ["csrc/decompose.cpp", "csrc/layout.cpp", "csrc/abi.cpp", "csrc/csf3.cpp", "csrc/host_check.cpp"]
+
+
+def build_host_check(sanitize: bool = True) -> str:
+    """CPU-only program that runs the host half of the library (CSR validation, decomposition,
+    packing, self-check, export, save / load / repack, the fibre builder) with the kernel
+    launchers stubbed out; with ``sanitize`` it is built with AddressSanitizer and
+    UndefinedBehaviorSanitizer, every report fatal.  g++ compiles the same sources hipcc does."""
+    srcs = [os.path.join(PKG_DIR, s) for s in HOST_SOURCES]
+    rocm_inc = os.path.join(os.path.dirname(os.path.dirname(_hipcc())), "include")
+    cmd = ["g++", "-O1", "-g", "-std=c++17", "-fopenmp", "-Wall", "-Wno-unused-result", "-Wno-unknown-pragmas",
+           "-D__HIP_PLATFORM_AMD__", "-I", rocm_inc, "-I", os.path.join(REPO_DIR, "include")]
+    if sanitize:
+        cmd += ["-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer"]
+    out = HOST_CHECK + ("_asan" if sanitize else "")
+    _run(cmd + srcs + ["-o", out])
+    return out
+
+
 def build_all() -> None:
     build_synth()
     build_oracle()
@@ -81,5 +105,11 @@ def build_all() -> None:
 if __name__ == "__main__":
     what = sys.argv[1:] or ["all"]
     for w in what:
-        {"all": build_all, "synth": build_synth, "oracle": build_oracle, "arrow": build_arrow}[w]()
+        if w == "--sanitize":
+            continue
+        if w == "arrow" and "--sanitize" in what:
+            build_host_check(sanitize=True)        # the host half of the library under ASan + UBSan
+            continue
+        {"all": build_all, "synth": build_synth, "oracle": build_oracle, "arrow": build_arrow,
+         "host_check": lambda: build_host_check(sanitize=False)}[w]()
     print("built:", ", ".join(what))

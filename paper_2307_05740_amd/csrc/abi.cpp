@@ -10,7 +10,6 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
-#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -42,36 +41,6 @@ int64_t env_int(const char* name, int64_t dflt) {
 
 constexpr size_t kAlign = 256;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
-
-// Scratch memory of arrow_spmm_static: one array per GPU the library is loaded on, held until the
-// process ends.  In host code the array's name is only a stand-in for the symbol; the device
-// address is looked up once per device (static_scratch) and that pointer is what kernels get.
-static __device__ __align__(256) unsigned char scratch[ARROW_STATIC_SCRATCH_BYTES];
-
-constexpr int kMaxDevices = 64;
-std::mutex g_scratch_mutex;
-unsigned char* g_scratch_ptr[kMaxDevices] = {};
-
-// device address of the current device's scratch array (NULL + error text on failure)
-unsigned char* static_scratch() {
-  int dev = -1;
-  hipError_t e = hipGetDevice(&dev);
-  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
-    g_err = std::string("static scratch: no usable current device: ") + hipGetErrorString(e);
-    return nullptr;
-  }
-  std::lock_guard<std::mutex> lock(g_scratch_mutex);
-  if (!g_scratch_ptr[dev]) {
-    void* ptr = nullptr;
-    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
-    if (e != hipSuccess || !ptr) {
-      g_err = std::string("static scratch: hipGetSymbolAddress failed: ") + hipGetErrorString(e);
-      return nullptr;
-    }
-    g_scratch_ptr[dev] = static_cast<unsigned char*>(ptr);
-  }
-  return g_scratch_ptr[dev];
-}
 
 enum KernelClass { kRows = 0, kChunks = 1, kReduce = 2, kStage = 3, kWindow = 4, kPanel = 5, kCorner = 6, kClasses = 7 };
 
@@ -528,7 +497,8 @@ int arrow_upload(arrow_handle* h, void* dev_buf, size_t bytes, void* stream) {
   h->dev = static_cast<unsigned char*>(dev_buf);
   // set-up on this device: look up the address of its copy of the static scratch array, so that
   // arrow_spmm_static never has to (a failure only matters to that call, which reports it)
-  (void)static_scratch();
+  std::string ignored;
+  (void)arrow::static_scratch(ignored);
   return ARROW_OK;
 }
 
@@ -565,8 +535,9 @@ int arrow_spmm_static(arrow_handle* h, const float* X, float* Y, int32_t k, void
                 "arrow_spmm with a workspace", k, need, (size_t)ARROW_STATIC_SCRATCH_BYTES);
   int rc = check_operands(h, X, Y, k, nullptr, 0);
   if (rc) return rc;
-  unsigned char* ws = static_scratch();   // resolved by arrow_upload on this device; a lookup, not an allocation
-  if (!ws) return ARROW_EHIP;
+  std::string why;
+  unsigned char* ws = arrow::static_scratch(why);   // resolved by arrow_upload on this device; a lookup, not an allocation
+  if (!ws) return fail(ARROW_EHIP, "%s", why.c_str());
   return product(h, X, Y, k, (hipStream_t)stream, ws, false);
 }
 

@@ -249,6 +249,10 @@ int launch_sddmm_chunks(const uint32_t* chunk_ptr, const uint32_t* chunk_mid, co
                         const float* V, int64_t v_rows, const float* Vh, float* S, int32_t k,
                         void* stream);
 
+// Device address of the current device's copy of the static scratch array of arrow_spmm_static
+// (static_scratch.hip); NULL and a description in `err` on failure.  A lookup, never an allocation.
+unsigned char* static_scratch(std::string& err);
+
 // Bare row gather (probe.hip), the yardstick of the measurements: `gathers` pseudo-random rows of
 // the n x k matrix X drawn from its first region_rows rows (per_die: from a region of its own for
 // every accelerator die; from_lds: the region is copied into LDS first) are read and summed.
