@@ -50,12 +50,18 @@ __global__ __launch_bounds__(kBlock) void probe_gather_kernel(const float* __res
   }
   const char* base = reinterpret_cast<const char*>(LDS ? win : X + base_row * (size_t)k);
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  const bool pow2 = (region_rows & (region_rows - 1)) == 0;
   for (uint32_t s = 0; s < (LDS ? kProbeLdsReps : 1) * (kProbePerWave / G); s += kProbeU) {
     uint32_t row[kProbeU];
     float4 x[kProbeU];
 #pragma unroll
     for (int u = 0; u < kProbeU; ++u)
-      row[u] = mix32(wave_id * (LDS ? kProbeLdsReps : 1) * kProbePerWave + (s + u) * G + g) % region_rows;
+    {
+      // a power-of-two region (every region bench.py uses) needs a mask, not a division: with the
+      // rows in LDS the division would be what the probe measures
+      const uint32_t h = mix32(wave_id * (LDS ? kProbeLdsReps : 1) * kProbePerWave + (s + u) * G + g);
+      row[u] = pow2 ? (h & (region_rows - 1)) : (h % region_rows);
+    }
 #pragma unroll
     for (int u = 0; u < kProbeU; ++u)
       x[u] = *reinterpret_cast<const float4*>(base + (size_t)row[u] * row_bytes + 16u * l);
