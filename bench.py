@@ -132,6 +132,25 @@ def gather_yardstick(torch, binding, X, n, k, dev, gathers=1 << 26):
     return res
 
 
+def hit_path_rate(torch, binding, k, dev):
+    """The product kernels' own rate when every gather hits the L2: a 4096 x 4096 operand with 2048
+    random entries per row (8.4 M entries, all of them in the chunk list) times an X of 4096 x k
+    (2 MiB at k = 128).  G rows/s of the whole product."""
+    rng = np.random.default_rng(7)
+    n, per_row = 4096, 2048
+    cols = np.sort(np.stack([rng.choice(n, per_row, replace=False) for _ in range(n)]), axis=1)
+    rowptr = np.arange(n + 1, dtype=np.int64) * per_row
+    vals = rng.uniform(-1, 1, n * per_row).astype(np.float32)
+    op = binding.ArrowSpMM(rowptr, cols.astype(np.int32).ravel(), vals, 512, device=dev)
+    X = torch.randn((n, k), device=dev)
+    Y = torch.empty_like(X)
+    for _ in range(3):
+        op.spmm(X, Y)
+    ms = per_call_events(torch, lambda: op.spmm(X, Y), 10)
+    op.close()
+    return round(n * per_row / (min(ms) * 1e-3) / 1e9, 2)
+
+
 def stored_traffic(path, launch_nnz, launch_items):
     """Counter bytes of a launch from a stored rocprofv3 summary, or None when there is none or when
     it was taken on another image (its entry / item counts differ from the live ones)."""
@@ -398,6 +417,12 @@ def main() -> int:
             if yard.get("l2_hit_2MiB_per_die"):
                 roofline["frac_of_l2_hit_yardstick"] = round(rate / yard["l2_hit_2MiB_per_die"], 3)
             roofline["product_Grows_per_s"] = round(nnz * l / (ms_per_step * 1e-3) / 1e9, 2)
+            if not sampled:
+                # the same kernels on an operand whose X fits the L2: what their hit path reaches
+                hp = hit_path_rate(torch, binding, k, dev)
+                roofline["hit_path_Grows_per_s"] = hp
+                if yard.get("l2_hit_2MiB_per_die"):
+                    roofline["hit_path_frac_of_l2_hit_yardstick"] = round(hp / yard["l2_hit_2MiB_per_die"], 3)
 
     # ---- quick correctness sanity + CPU baseline: the oracle on a bounded row sample ----------
     cpu_baseline = None

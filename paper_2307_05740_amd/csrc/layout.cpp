@@ -281,6 +281,14 @@ int pack_levels(int64_t n, int32_t b, const std::vector<HostLevel>& levels, cons
     // those entries reuse the span often enough to pay for staging it.
     std::vector<uint8_t> taken(L.n_i, 0);
     int64_t nnz_w = 0;
+    // A row joins a window tile only when the entries it reads from memory there (first block
+    // column; other blocks once levels are fused) do not outnumber its diagonal-block entries, or
+    // are few anyway: the window kernel reads those one lane group per row, which is the slow way
+    // to handle a long row.
+    auto window_row_ok = [&](int64_t len, int64_t in_block) {
+      const int64_t outside = len - in_block;
+      return outside <= in_block || outside <= short_max;
+    };
     if (opt.window_span > 0 && L.n_i > b) {
       const int64_t span_cap = opt.window_span, rows_cap = opt.window_tile_rows < 1 ? 1 : opt.window_tile_rows;
       for (int64_t blk0 = b; blk0 < L.n_i; blk0 += b) {
@@ -296,6 +304,7 @@ int pack_levels(int64_t n, int32_t b, const std::vector<HostLevel>& levels, cons
             const int32_t* cd = std::lower_bound(cb, ce, (int32_t)blk0);
             const int32_t* cx = std::lower_bound(cd, ce, (int32_t)blk1);
             if (cd == cx) continue;                                       // no diagonal-block entry
+            if (!window_row_ok(ce - cb, cx - cd)) continue;               // the row stays in the ordinary lists
             const int64_t nmin = std::min<int64_t>(cmin, *cd), nmax = std::max<int64_t>(cmax, *(cx - 1));
             if (nmax - nmin + 1 > span_cap) break;
             cmin = nmin; cmax = nmax; dnnz += cx - cd;
@@ -309,6 +318,13 @@ int pack_levels(int64_t n, int32_t b, const std::vector<HostLevel>& levels, cons
             for (int64_t p = p0; p < p1; ++p) {
               const int64_t len = L.rowptr[p + 1] - L.rowptr[p];
               if (len == 0 && li > 0) continue;
+              {
+                const int32_t* cb = L.colpos.data() + L.rowptr[p];
+                const int32_t* ce = cb + len;
+                const int32_t* cd = std::lower_bound(cb, ce, (int32_t)blk0);
+                const int32_t* cx = std::lower_bound(cd, ce, (int32_t)blk1);
+                if (!window_row_ok(len, cx - cd)) continue;
+              }
               taken[p] = 1;
               P.wrow_pos.push_back((int32_t)p);
               nnz_w += len;

@@ -489,6 +489,37 @@ def test_dense_corner_takes_the_leading_entries_of_its_rows(monkeypatch):
     binding.arrow_destroy(h)
 
 
+def test_long_rows_do_not_become_lds_window_rows():
+    """Rows that spread over many blocks (most of their entries belong to later levels and join
+    the level-0 row when levels are fused) are not run as LDS-window rows, whose entries outside
+    the window are read by one lane group per row; rows that live in their diagonal block are."""
+    rng = np.random.default_rng(3)
+    n, b, per_row = 2048, 256, 512
+    cols = np.sort(np.stack([rng.choice(n, per_row, replace=False) for _ in range(n)]), axis=1)
+    rp = np.arange(n + 1, dtype=np.int64) * per_row
+    h = binding.arrow_decompose(rp, cols.astype(np.int32).ravel(), rng.uniform(-1, 1, n * per_row).astype(np.float32), b)
+    try:
+        binding.arrow_self_check(h)
+        li = binding.arrow_level_info(h, 0)
+        assert li["nnz_window"] == 0 and li["nnz_fused"] > 0
+        assert li["nnz_chunks"] + li["nnz_rows"] == n * per_row
+    finally:
+        binding.arrow_destroy(h)
+    # block-diagonal operand with a few far entries per row: the rows still qualify
+    rows = np.repeat(np.arange(n), 24)
+    c = (rows // b) * b + rng.integers(0, b, rows.shape[0])
+    far = rng.integers(0, n, (n, 2))
+    key = np.unique(np.concatenate([rows * n + c, np.repeat(np.arange(n), 2) * n + far.ravel()]))
+    rp, ci, va = csr_from_coo(n, key // n, key % n, rng.uniform(-1, 1, len(key)))
+    h = binding.arrow_decompose(rp, ci, va, b)
+    try:
+        binding.arrow_self_check(h)
+        li = binding.arrow_level_info(h, 0)
+        assert li["window_tiles"] > 0 and li["nnz_window"] > 0.5 * len(key)
+    finally:
+        binding.arrow_destroy(h)
+
+
 def test_head_order_inside_the_head(monkeypatch):
     """The arrow shape only fixes WHICH vertices are in the head; inside it they sit in id order
     (so that position order follows the caller's column order), or by falling degree on request.
