@@ -8,7 +8,7 @@
 //   region of 128 MiB, per_die = 0          : the size of the staged head of the headline workload
 //   the whole matrix (GiBs)                 : HBM
 //   from_lds = 1                            : the region (at most 64 KiB) is copied into LDS first
-// The row numbers come from a 32-bit mixing function of the gather's index, so a run is repeatable.
+// The row numbers come from a hash of the gather's index, so a run is repeatable.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -59,8 +59,10 @@ __global__ __launch_bounds__(kBlock) void probe_gather_kernel(const float* __res
     {
       // a power-of-two region (every region bench.py uses) needs a mask, not a division: with the
       // rows in LDS the division would be what the probe measures
-      const uint32_t h = mix32(wave_id * (LDS ? kProbeLdsReps : 1) * kProbePerWave + (s + u) * G + g);
-      row[u] = pow2 ? (h & (region_rows - 1)) : (h % region_rows);
+      const uint32_t idx = wave_id * (LDS ? kProbeLdsReps : 1) * kProbePerWave + (s + u) * G + g;
+      // a multiplicative hash (one multiply, one shift) where a mask selects the row; the full
+      // mixing function only where a division is needed anyway
+      row[u] = pow2 ? (((idx * 0x9E3779B1u) >> 9) & (region_rows - 1)) : (mix32(idx) % region_rows);
     }
 #pragma unroll
     for (int u = 0; u < kProbeU; ++u)
