@@ -291,6 +291,9 @@ def main() -> int:
                          "n*k*4 written each) so that counter runs can be scaled")
     ap.add_argument("--no-profile-pass", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--no-gather-yardstick", action="store_true", help="skip the bare row-gather probes")
+    ap.add_argument("--hit-path", action="store_true",
+                    help="also time the product kernels on a small operand whose X fits the L2 (every gather a "
+                         "hit) and report their rate against the L2-hit yardstick")
     ap.add_argument("--kc", type=int, default=None)
     ap.add_argument("--op", choices=("spmm", "sddmm", "mttkrp"), default="spmm",
                     help="spmm: Y = A.X (the headline); sddmm: S = A .* (U V^T) on the same layout; "
@@ -417,7 +420,7 @@ def main() -> int:
             if yard.get("l2_hit_2MiB_per_die"):
                 roofline["frac_of_l2_hit_yardstick"] = round(rate / yard["l2_hit_2MiB_per_die"], 3)
             roofline["product_Grows_per_s"] = round(nnz * l / (ms_per_step * 1e-3) / 1e9, 2)
-            if not sampled:
+            if args.hit_path and not sampled:
                 # the same kernels on an operand whose X fits the L2: what their hit path reaches
                 hp = hit_path_rate(torch, binding, k, dev)
                 roofline["hit_path_Grows_per_s"] = hp
