@@ -408,6 +408,10 @@ def main() -> int:
         # the counter bytes over the live launch time, and how much of them the method asks for
         roofline["counter_GBps"] = round(traffic / (avg_ms * 1e-3) / 1e9, 1)
         roofline["useful_fraction"] = round(bytes_per_launch / traffic, 4)
+    # the plain device-to-device copy Y <- X (n*k*4 bytes read and as many written): what a pure
+    # stream reaches on this device, next to the 8 TB/s peak figure
+    copy_ms = min(per_call_events(torch, lambda: Y.copy_(X), 5))
+    roofline["copy_yardstick_GBps"] = round(2.0 * n * k * 4 / (copy_ms * 1e-3) / 1e9, 1)
     if not args.no_gather_yardstick:
         # every stored entry of the launch gathers one row of 4k bytes: its rate against the bare
         # gather of rows that all hit the L2 is how far the kernel is from the device's limit for
