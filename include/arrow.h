@@ -222,7 +222,11 @@ int arrow_export_level(const arrow_handle *h, int32_t level, int32_t *perm,
  * Host-only consistency check of the packed device image against the levels it was built from:
  * offsets ordered and in range, row ids inside X / the staging buffer / the LDS windows, every
  * partial slot written once, every row of every level produced exactly once from exactly its
- * entries.  Returns ARROW_OK or ARROW_EINTERNAL (text in arrow_last_error).  O(nnz), no GPU.
+ * entries, the entry map a bijection that keeps row and value; with fused levels the execution
+ * form (later levels' entries listed with the level-0 rows) is rebuilt and compared entry by entry
+ * with the levels first; panel streams and corner tiles (items and panels partition the tiles,
+ * runs ordered and never sharing a row) are covered as well.
+ * Returns ARROW_OK or ARROW_EINTERNAL (text in arrow_last_error).  O(nnz log nnz), no GPU.
  */
 int arrow_self_check(const arrow_handle *h);
 
